@@ -1,0 +1,182 @@
+/*
+ * libdash: the hot path of DASH (Delta Attention Selective Halting) for one GPU (gfx950).
+ *
+ * One prefill self-attention layer executed over only the still-active tokens
+ * (Sec. 3.4: every block runs on the compacted active sequence), followed by the
+ * per-token delta-attention score (Eq. 2), the halting decision (Eq. 3) and the
+ * stream compaction that hands the next layer a shorter sequence (Alg. 1 step 4).
+ *
+ * Conventions for every entry point
+ *   - Plain C ABI. Pointers marked "device" are GPU global memory owned by the
+ *     caller; "host" pointers are ordinary host memory. The library allocates
+ *     nothing and keeps no state between calls.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream); calls return after enqueue and never synchronise.
+ *   - Every device pointer must be 16-byte aligned. Matrices are row-major and
+ *     dense (no padding between rows).
+ *   - Errors are reported as a dash_status; argument errors are found on the host
+ *     before anything is launched, HIP launch errors map to DASH_ERR_HIP.
+ *   - dtype selects the storage type of x, q, k, v, w_o, O, x_next, x_compact:
+ *     DASH_BF16 (MFMA kernels, fp32 accumulation and fp32 softmax) or DASH_F32
+ *     (plain fp32 kernels). Scores and norm partials are always fp32.
+ */
+#ifndef DASH_H
+#define DASH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DASH_OK = 0,
+    DASH_ERR_INVALID_ARG = -1,
+    DASH_ERR_UNSUPPORTED = -2,
+    DASH_ERR_WORKSPACE = -3,
+    DASH_ERR_HIP = -4
+} dash_status;
+
+typedef enum { DASH_BF16 = 0, DASH_F32 = 1 } dash_dtype;
+
+/* NONE: no token halts (layers before the start layer l_s of the single-shot
+ * schedule, Sec. 3.2); scores are still produced. THRESHOLD: the cut drawn as a
+ * threshold line in Fig. 8. TOPK: Eq. 3. */
+typedef enum { DASH_RULE_NONE = 0, DASH_RULE_THRESHOLD = 1, DASH_RULE_TOPK = 2 } dash_rule;
+
+/* REL: ||U_t||_2 / max(||H_t||_2, 1e-30), H_t the row entering the block (the
+ * "relative" delta-attention of Fig. 1). ABS: ||U_t||_2 (Eq. 2). */
+typedef enum { DASH_SCORE_REL = 0, DASH_SCORE_ABS = 1 } dash_score_kind;
+
+typedef struct {
+    int32_t d;            /* hidden size (columns of x and of w_o) */
+    int32_t n_q_heads;    /* query heads; n_q_heads * head_dim = rows of w_o */
+    int32_t n_kv_heads;   /* key/value heads; must divide n_q_heads */
+    int32_t head_dim;     /* 64 or 128 */
+    int32_t dtype;        /* dash_dtype */
+    int32_t causal;       /* non-zero: key j visible to query i iff its original position
+                             active_idx[j] <= active_idx[i] */
+    float softmax_scale;  /* <= 0 selects 1/sqrt(head_dim) */
+    int32_t rule;         /* dash_rule */
+    int32_t score_kind;   /* dash_score_kind */
+    float tau;            /* THRESHOLD: a row halts iff score < tau (equal or NaN is kept) */
+    int32_t k_keep;       /* TOPK: rows kept in total, protected rows included;
+                             < 0 selects floor((1 - rho) * n_active)  (Eq. 3) */
+    float rho;            /* pruning ratio in [0,1), used only when k_keep < 0 */
+    int32_t keep_first_n; /* protected ranks at the head of the current active order (App. A) */
+    int32_t keep_last_n;  /* protected ranks at its tail; protected rows never halt */
+} dash_layer_params;
+
+/* Optional per-stage timing. When a dash_profile is passed to dash_attn_layer it
+ * records HIP events on the launch stream around the four stages; read them back
+ * with dash_profile_read after the stream has been synchronised by the caller. */
+typedef struct dash_profile dash_profile;
+#define DASH_N_STAGES 4 /* 0 flash attention, 1 W_o+residual+norms, 2 score+decision, 3 compaction */
+
+dash_profile *dash_profile_create(void);            /* host; NULL on failure */
+void dash_profile_destroy(dash_profile *);          /* host */
+/* host; ms[DASH_N_STAGES] receives the stage durations of the LAST profiled call.
+ * The stream must be idle (caller synchronised). */
+dash_status dash_profile_read(dash_profile *, float *ms);
+
+/* Bytes of device workspace dash_attn_layer needs for up to n_capacity active rows
+ * (0 on invalid params). Host. */
+size_t dash_workspace_bytes(const dash_layer_params *params, int32_t n_capacity);
+
+/* Number of fp32 (sum delta^2, sum x^2) pairs per row that the projection stage
+ * writes and the score stage reads; depends only on params->d and dtype. Host. */
+int32_t dash_norm_partials_per_row(const dash_layer_params *params);
+
+/*
+ * The whole layer step on the active rows (Eq. 1-3, Alg. 1 steps 4-6 and 9-13):
+ *   O      = Attn(q, k, v)                    causal GQA softmax attention
+ *   delta  = O * w_o                          U of Eq. 1 (before the residual add)
+ *   x_next = x + delta                        for ALL n_active rows, halted-now rows included
+ *   scores = ||delta_t|| [/ ||x_t||]          Eq. 2 from the fp32 accumulators
+ *   halt   = decision(scores)                 params->rule
+ *   new_active_idx, x_compact, n_active_out = stable compaction of the kept rows
+ *
+ * device inputs : x [n,d], q [n,Hq,dh], k,v [n,Hkv,dh], w_o [Hq*dh, d] (delta = O @ w_o),
+ *                 active_idx [n] int32, strictly increasing original positions
+ * host input    : n_active (rows), >= 0; 0 is a valid no-op that writes n_active_out = 0
+ * device outputs: x_next [n,d]; scores [n] fp32; halt_mask [n] uint8 (1 = halted);
+ *                 x_compact [n,d] (first n_active_out rows valid, bitwise copies of kept
+ *                 x_next rows); new_active_idx [n] (first n_active_out valid);
+ *                 n_active_out: ONE device int32
+ *                 delta_dbg: NULL, or fp32 [n,d] that receives delta
+ * workspace     : device, >= dash_workspace_bytes(params, n_active), 256-byte aligned
+ * profile       : NULL or a dash_profile
+ */
+dash_status dash_attn_layer(const dash_layer_params *params, const void *x, const void *q, const void *k,
+                            const void *v, const void *w_o, const int32_t *active_idx, int32_t n_active,
+                            void *x_next, float *scores, uint8_t *halt_mask, void *x_compact,
+                            int32_t *new_active_idx, int32_t *n_active_out, float *delta_dbg,
+                            void *workspace, size_t workspace_bytes, dash_profile *profile,
+                            void *hip_stream);
+
+/* ---- stage-level entry points (same conventions), so each kernel can be tested and timed alone ---- */
+
+/* Stage 0. Attention of Eq. 1 without the output projection: o [n, Hq*dh] in params->dtype.
+ * Tiled online-softmax forward; the probability matrix never reaches HBM. */
+dash_status dash_flash_fwd(const dash_layer_params *params, const void *q, const void *k, const void *v,
+                           const int32_t *active_idx, int32_t n_active, void *o, void *hip_stream);
+
+/* Stage 1. delta = o @ w_o; x_next = x + delta (Sec. 3.1, Alg. 1 step 6); per-row partial sums of
+ * delta^2 and x^2 taken from the fp32 accumulators: norm_partials [n, P, 2] fp32 with
+ * P = dash_norm_partials_per_row(params). delta_dbg NULL or fp32 [n,d].
+ * workspace: device scratch of dash_workspace_bytes(params, n) (only part is used). */
+dash_status dash_wo_residual_rownorm(const dash_layer_params *params, const void *o, const void *w_o,
+                                     const void *x, int32_t n, void *x_next, float *norm_partials,
+                                     float *delta_dbg, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+
+/* Stage 2. scores (Eq. 2) from the partials, then the decision (Eq. 3 / threshold).
+ * chunk_keep_counts: device int32 [ceil(n/64)], kept rows per 64-row chunk, consumed by dash_compact.
+ * workspace: device scratch, >= 8 KiB (TopK selection state). */
+dash_status dash_score_decide(const dash_layer_params *params, const float *norm_partials, int32_t n,
+                              float *scores, uint8_t *halt_mask, int32_t *chunk_keep_counts,
+                              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Stage 3. Stable stream compaction by halt_mask (Alg. 1 step 4): prefix sum of kept flags, gather of
+ * hidden rows and original positions. chunk_keep_counts as written by dash_score_decide, or NULL to
+ * have them recomputed from halt_mask into workspace (>= 4*ceil(n/64) bytes). */
+dash_status dash_compact(const dash_layer_params *params, const uint8_t *halt_mask,
+                         const int32_t *chunk_keep_counts, const int32_t *active_idx, const void *x_next,
+                         int32_t n, void *x_compact, int32_t *new_active_idx, int32_t *n_active_out,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Standalone score of Eq. 2 from a stored fp32 delta [n,d] and x [n,d] (dtype): one pass over HBM. */
+dash_status dash_score_rows(const float *delta, const void *x, int32_t n, int32_t d, int32_t dtype,
+                            int32_t score_kind, float *scores, void *hip_stream);
+
+/* Front end of a layer in a chain (Eq. 1's LN and the q/k/v projections, which sit before the path):
+ * h = x / sqrt(mean(x^2) + 1e-6) (unit gain); q = h @ w_q [d, Hq*dh]; k = h @ w_k; v = h @ w_v
+ * [d, Hkv*dh]. bf16 only. h_scratch: device [n,d] bf16. */
+dash_status dash_rmsnorm_qkv(const dash_layer_params *params, const void *x, const void *w_q,
+                             const void *w_k, const void *w_v, int32_t n, void *q, void *k, void *v,
+                             void *h_scratch, void *hip_stream);
+
+/* Debug aid: counts rows where active_idx is not strictly increasing or lies outside [0, N)
+ * (N < 0: no upper bound) into ONE device int32 *violations. */
+dash_status dash_validate_active_idx(const int32_t *active_idx, int32_t n, int32_t N, int32_t *violations,
+                                     void *hip_stream);
+
+/* Host arithmetic: tokens kept out of n.
+ * paper_impl_rounding == 0: floor((1 - rho) n) (Eq. 3);
+ * otherwise n - round(rho * (n - keep_first_n - keep_last_n)) (App. A, caption of Table 5).
+ * Returns -1 on invalid arguments. */
+int64_t dash_keep_count(int64_t n, double rho, int32_t keep_first_n, int32_t keep_last_n,
+                        int32_t paper_impl_rounding);
+
+/* Algorithmic floating-point operations of stages 0+1 for n active rows: causal triangle
+ * 4*dh*Hq*n(n+1)/2 (or the full square when not causal) plus 2*n*(Hq*dh)*d. Host. */
+double dash_layer_flops(const dash_layer_params *params, int64_t n);
+
+const char *dash_status_string(dash_status);
+const char *dash_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DASH_H */

@@ -1,0 +1,276 @@
+// Host side of libdash: argument validation, workspace carving, stage sequencing. See include/dash.h.
+#include <math.h>
+#include <new>
+
+#include "common.h"
+
+using namespace dash;
+
+struct dash_profile {
+    hipEvent_t ev[DASH_N_STAGES + 1];
+    bool recorded;
+};
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+size_t elem_size(int dtype) { return dtype == DASH_BF16 ? 2 : 4; }
+
+dash_status check_params(const dash_layer_params* p) {
+    if (!p) return DASH_ERR_INVALID_ARG;
+    if (p->dtype != DASH_BF16 && p->dtype != DASH_F32) return DASH_ERR_INVALID_ARG;
+    if (p->d <= 0 || p->n_q_heads <= 0 || p->n_kv_heads <= 0) return DASH_ERR_INVALID_ARG;
+    if (p->n_q_heads % p->n_kv_heads != 0) return DASH_ERR_INVALID_ARG;
+    if (p->head_dim != 64 && p->head_dim != 128) return DASH_ERR_UNSUPPORTED;
+    if ((p->d * (int)elem_size(p->dtype)) % 16 != 0) return DASH_ERR_UNSUPPORTED;  // 16-byte row vectors
+    if (p->rule != DASH_RULE_NONE && p->rule != DASH_RULE_THRESHOLD && p->rule != DASH_RULE_TOPK)
+        return DASH_ERR_INVALID_ARG;
+    if (p->score_kind != DASH_SCORE_REL && p->score_kind != DASH_SCORE_ABS) return DASH_ERR_INVALID_ARG;
+    if (p->keep_first_n < 0 || p->keep_last_n < 0) return DASH_ERR_INVALID_ARG;
+    if (p->rule == DASH_RULE_TOPK && p->k_keep < 0 && !(p->rho >= 0.f && p->rho < 1.f))
+        return DASH_ERR_INVALID_ARG;
+    return DASH_OK;
+}
+
+struct Workspace {
+    size_t o_off, partials_off, counts_off, decide_off, total;
+};
+
+Workspace carve(const dash_layer_params& p, int64_t n) {
+    Workspace w;
+    size_t off = 0;
+    w.o_off = off;
+    off = align_up(off + (size_t)n * p.n_q_heads * p.head_dim * elem_size(p.dtype), 256);
+    w.partials_off = off;
+    off = align_up(off + (size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float), 256);
+    const size_t n_chunks = (size_t)(n + kChunkRows - 1) / kChunkRows;
+    w.counts_off = off;
+    off = align_up(off + n_chunks * sizeof(int32_t), 256);
+    w.decide_off = off;
+    off = align_up(off + decide_workspace_bytes() + n_chunks * sizeof(int32_t), 256);
+    w.total = off;
+    return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dash_status_string(dash_status s) {
+    switch (s) {
+        case DASH_OK: return "ok";
+        case DASH_ERR_INVALID_ARG: return "invalid argument";
+        case DASH_ERR_UNSUPPORTED: return "unsupported shape or type";
+        case DASH_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case DASH_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+const char* dash_version(void) { return "libdash 0.1 (gfx950)"; }
+
+int64_t dash_keep_count(int64_t n, double rho, int32_t keep_first_n, int32_t keep_last_n,
+                        int32_t paper_impl_rounding) {
+    if (n < 0 || !(rho >= 0.0 && rho < 1.0) || keep_first_n < 0 || keep_last_n < 0) return -1;
+    if (!paper_impl_rounding) return (int64_t)floor((1.0 - rho) * (double)n);
+    const int64_t n_fix = (int64_t)keep_first_n + keep_last_n;
+    if (n <= n_fix) return n;
+    return n - llround(rho * (double)(n - n_fix));
+}
+
+double dash_layer_flops(const dash_layer_params* p, int64_t n) {
+    if (check_params(p) != DASH_OK || n < 0) return 0.0;
+    const double nn = (double)n, Da = (double)p->n_q_heads * p->head_dim;
+    const double pairs = p->causal ? nn * (nn + 1.0) / 2.0 : nn * nn;
+    return 4.0 * p->head_dim * p->n_q_heads * pairs + 2.0 * nn * Da * (double)p->d;
+}
+
+int32_t dash_norm_partials_per_row(const dash_layer_params* p) {
+    if (check_params(p) != DASH_OK) return 0;
+    return norm_partials_per_row(p->d, p->dtype);
+}
+
+size_t dash_workspace_bytes(const dash_layer_params* p, int32_t n_capacity) {
+    if (check_params(p) != DASH_OK || n_capacity < 0) return 0;
+    return carve(*p, n_capacity).total;
+}
+
+dash_profile* dash_profile_create(void) {
+    dash_profile* pr = new (std::nothrow) dash_profile;
+    if (!pr) return nullptr;
+    pr->recorded = false;
+    for (int i = 0; i <= DASH_N_STAGES; ++i) {
+        if (hipEventCreate(&pr->ev[i]) != hipSuccess) {
+            for (int k = 0; k < i; ++k) (void)hipEventDestroy(pr->ev[k]);
+            delete pr;
+            return nullptr;
+        }
+    }
+    return pr;
+}
+
+void dash_profile_destroy(dash_profile* pr) {
+    if (!pr) return;
+    for (int i = 0; i <= DASH_N_STAGES; ++i) (void)hipEventDestroy(pr->ev[i]);
+    delete pr;
+}
+
+dash_status dash_profile_read(dash_profile* pr, float* ms) {
+    if (!pr || !ms || !pr->recorded) return DASH_ERR_INVALID_ARG;
+    for (int i = 0; i < DASH_N_STAGES; ++i)
+        DASH_HIP_CHECK(hipEventElapsedTime(&ms[i], pr->ev[i], pr->ev[i + 1]));
+    return DASH_OK;
+}
+
+dash_status dash_flash_fwd(const dash_layer_params* p, const void* q, const void* k, const void* v,
+                           const int32_t* active_idx, int32_t n, void* o, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!q || !k || !v || !active_idx || !o) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DASH_ERR_INVALID_ARG;
+    return launch_flash_fwd(*p, q, k, v, active_idx, n, o, (hipStream_t)hip_stream);
+}
+
+dash_status dash_wo_residual_rownorm(const dash_layer_params* p, const void* o, const void* w_o,
+                                     const void* x, int32_t n, void* x_next, float* norm_partials,
+                                     float* delta_dbg, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!o || !w_o || !x || !x_next || !norm_partials) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(o) || !aligned16(w_o) || !aligned16(x) || !aligned16(x_next) ||
+        !aligned16(norm_partials) || !aligned16(delta_dbg))
+        return DASH_ERR_INVALID_ARG;
+    return launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, norm_partials, delta_dbg,
+                                      (hipStream_t)hip_stream);
+}
+
+dash_status dash_score_decide(const dash_layer_params* p, const float* norm_partials, int32_t n,
+                              float* scores, uint8_t* halt_mask, int32_t* chunk_keep_counts,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!norm_partials || !scores || !halt_mask || !chunk_keep_counts) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(norm_partials)) return DASH_ERR_INVALID_ARG;
+    const size_t need = decide_workspace_bytes() + (size_t)((n + kChunkRows - 1) / kChunkRows) * 4;
+    if (p->rule == DASH_RULE_TOPK && (!workspace || workspace_bytes < need || !aligned16(workspace)))
+        return DASH_ERR_WORKSPACE;
+    return launch_score_decide(*p, norm_partials, norm_partials_per_row(p->d, p->dtype), n, scores,
+                               halt_mask, chunk_keep_counts, workspace, (hipStream_t)hip_stream);
+}
+
+dash_status dash_compact(const dash_layer_params* p, const uint8_t* halt_mask,
+                         const int32_t* chunk_keep_counts, const int32_t* active_idx, const void* x_next,
+                         int32_t n, void* x_compact, int32_t* new_active_idx, int32_t* n_active_out,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0 || !n_active_out) return DASH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n > 0) {
+        if (!halt_mask || !active_idx || !x_next || !x_compact || !new_active_idx)
+            return DASH_ERR_INVALID_ARG;
+        if (!aligned16(x_next) || !aligned16(x_compact)) return DASH_ERR_INVALID_ARG;
+        if (!chunk_keep_counts) {
+            const size_t need = (size_t)((n + kChunkRows - 1) / kChunkRows) * 4;
+            if (!workspace || workspace_bytes < need) return DASH_ERR_WORKSPACE;
+            st = launch_chunk_counts(halt_mask, n, (int32_t*)workspace, s);
+            if (st != DASH_OK) return st;
+            chunk_keep_counts = (const int32_t*)workspace;
+        }
+    }
+    return launch_compact(halt_mask, chunk_keep_counts, active_idx, x_next, n,
+                          p->d * (int)elem_size(p->dtype), x_compact, new_active_idx, n_active_out, s);
+}
+
+dash_status dash_score_rows(const float* delta, const void* x, int32_t n, int32_t d, int32_t dtype,
+                            int32_t score_kind, float* scores, void* hip_stream) {
+    if (n < 0 || d <= 0 || d % 8 != 0) return DASH_ERR_INVALID_ARG;
+    if (dtype != DASH_BF16 && dtype != DASH_F32) return DASH_ERR_INVALID_ARG;
+    if (score_kind != DASH_SCORE_REL && score_kind != DASH_SCORE_ABS) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!delta || !scores || (score_kind == DASH_SCORE_REL && !x)) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(delta) || !aligned16(x)) return DASH_ERR_INVALID_ARG;
+    return launch_score_rows(delta, x, n, d, dtype, score_kind, scores, (hipStream_t)hip_stream);
+}
+
+dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const void* w_q, const void* w_k,
+                             const void* w_v, int32_t n, void* q, void* k, void* v, void* h_scratch,
+                             void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
+    if (p->d % 32 != 0) return DASH_ERR_UNSUPPORTED;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!x || !w_q || !w_k || !w_v || !q || !k || !v || !h_scratch) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_q) || !aligned16(w_k) || !aligned16(w_v) || !aligned16(q) ||
+        !aligned16(k) || !aligned16(v) || !aligned16(h_scratch))
+        return DASH_ERR_INVALID_ARG;
+    return launch_rmsnorm_qkv(*p, x, w_q, w_k, w_v, n, q, k, v, h_scratch, (hipStream_t)hip_stream);
+}
+
+dash_status dash_validate_active_idx(const int32_t* active_idx, int32_t n, int32_t N, int32_t* violations,
+                                     void* hip_stream) {
+    if (n < 0 || !violations || (n > 0 && !active_idx)) return DASH_ERR_INVALID_ARG;
+    return launch_validate_idx(active_idx, n, N, violations, (hipStream_t)hip_stream);
+}
+
+dash_status dash_attn_layer(const dash_layer_params* p, const void* x, const void* q, const void* k,
+                            const void* v, const void* w_o, const int32_t* active_idx, int32_t n,
+                            void* x_next, float* scores, uint8_t* halt_mask, void* x_compact,
+                            int32_t* new_active_idx, int32_t* n_active_out, float* delta_dbg,
+                            void* workspace, size_t workspace_bytes, dash_profile* profile,
+                            void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0 || !n_active_out) return DASH_ERR_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (n == 0)
+        return launch_compact(nullptr, nullptr, nullptr, nullptr, 0, 0, nullptr, nullptr, n_active_out, s);
+    if (!x || !q || !k || !v || !w_o || !active_idx || !x_next || !scores || !halt_mask || !x_compact ||
+        !new_active_idx)
+        return DASH_ERR_INVALID_ARG;
+    const void* ptrs[] = {x, q, k, v, w_o, x_next, x_compact, delta_dbg};
+    for (const void* ptr : ptrs)
+        if (!aligned16(ptr)) return DASH_ERR_INVALID_ARG;
+    const Workspace w = carve(*p, n);
+    if (!workspace || workspace_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return DASH_ERR_WORKSPACE;
+    char* ws = static_cast<char*>(workspace);
+    void* o = ws + w.o_off;
+    float* partials = reinterpret_cast<float*>(ws + w.partials_off);
+    int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts_off);
+    void* decide_ws = ws + w.decide_off;
+
+    if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[0], s));
+    st = launch_flash_fwd(*p, q, k, v, active_idx, n, o, s);
+    if (st != DASH_OK) return st;
+    if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[1], s));
+    st = launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, partials, delta_dbg, s);
+    if (st != DASH_OK) return st;
+    if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[2], s));
+    st = launch_score_decide(*p, partials, norm_partials_per_row(p->d, p->dtype), n, scores, halt_mask,
+                             counts, decide_ws, s);
+    if (st != DASH_OK) return st;
+    if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[3], s));
+    st = launch_compact(halt_mask, counts, active_idx, x_next, n, p->d * (int)elem_size(p->dtype), x_compact,
+                        new_active_idx, n_active_out, s);
+    if (st != DASH_OK) return st;
+    if (profile) {
+        DASH_HIP_CHECK(hipEventRecord(profile->ev[4], s));
+        profile->recorded = true;
+    }
+    return DASH_OK;
+}
+
+}  // extern "C"

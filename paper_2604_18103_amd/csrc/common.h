@@ -1,0 +1,72 @@
+// Shared declarations of the libdash kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dash.h"
+
+namespace dash {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kWave = 64;
+constexpr float kNormEps = 1e-30f;  // floor on ||x_t|| in the relative score
+constexpr int kChunkRows = 64;      // rows per keep-count chunk (one wave ballot)
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(__bf16 v) { return (float)v; }
+template <typename T>
+__device__ __forceinline__ T from_float(float v);
+template <>
+__device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ __bf16 from_float<__bf16>(float v) { return (__bf16)v; }  // round to nearest even
+
+// Row is in the protected prefix/suffix of the current active order (App. A).
+__device__ __forceinline__ bool row_protected(int i, int n, int n_first, int n_last) {
+    return i < n_first || i >= n - n_last;
+}
+
+#define DASH_HIP_CHECK(expr)                     \
+    do {                                         \
+        if ((expr) != hipSuccess) return DASH_ERR_HIP; \
+    } while (0)
+
+inline dash_status launch_status() { return hipGetLastError() == hipSuccess ? DASH_OK : DASH_ERR_HIP; }
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- stage launchers (implemented in the .hip files; all arguments validated by the caller) ----
+
+// flash_fwd.hip
+dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const void* k, const void* v,
+                             const int32_t* active_idx, int n, void* o, hipStream_t s);
+// wo_gemm.hip
+int norm_partials_per_row(int d, int dtype);
+dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o, const void* w_o,
+                                       const void* x, int n, void* x_next, float* partials,
+                                       float* delta_dbg, hipStream_t s);
+dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
+                               const void* w_v, int n, void* q, void* k, void* v, void* h, hipStream_t s);
+// score_decide.hip
+size_t decide_workspace_bytes();
+dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,
+                                float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
+                                hipStream_t s);
+dash_status launch_score_rows(const float* delta, const void* x, int n, int d, int dtype, int kind,
+                              float* scores, hipStream_t s);
+// compact.hip
+dash_status launch_chunk_counts(const uint8_t* halt, int n, int32_t* chunk_counts, hipStream_t s);
+dash_status launch_compact(const uint8_t* halt, const int32_t* chunk_counts, const int32_t* active_idx,
+                           const void* x_next, int n, int row_bytes, void* x_compact,
+                           int32_t* new_active_idx, int32_t* n_active_out, hipStream_t s);
+dash_status launch_validate_idx(const int32_t* idx, int n, int N, int32_t* violations, hipStream_t s);
+
+}  // namespace dash

@@ -1,0 +1,239 @@
+// Per-token delta-attention score (Eq. 2, or its relative form) and the halting decision
+// (Eq. 3 TopK, or the threshold line of Fig. 8). HBM/latency-bound: a few bytes per row.
+//
+// Scores are finished here from per-row partial sums of squares that the projection stage took from
+// its fp32 accumulators: partials [P, n, 2] = (sum delta^2, sum x^2), summed over P in a fixed order
+// so the result is bit-reproducible.
+#include "common.h"
+
+namespace dash {
+
+__device__ __forceinline__ float finish_score(const float* __restrict__ partials, int P, int n, int row,
+                                              int score_kind) {
+    float sd = 0.f, sx = 0.f;
+    for (int p = 0; p < P; ++p) {
+        const float2 v = *reinterpret_cast<const float2*>(partials + ((size_t)p * n + row) * 2);
+        sd += v.x;
+        sx += v.y;
+    }
+    const float nd = sqrtf(sd);
+    if (score_kind == DASH_SCORE_ABS) return nd;
+    return nd / fmaxf(sqrtf(sx), kNormEps);
+}
+
+// rule NONE / THRESHOLD: score, flag and the chunk's kept count in one pass. One wave per 64-row chunk.
+__global__ __launch_bounds__(256) void score_threshold_kernel(
+    const float* __restrict__ partials, int P, int n, int score_kind, int rule, float tau, int n_first,
+    int n_last, float* __restrict__ scores, uint8_t* __restrict__ halt, int32_t* __restrict__ chunk_counts) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    const int lane = threadIdx.x % kWave;
+    bool keep = false;
+    if (row < n) {
+        const float s = finish_score(partials, P, n, row, score_kind);
+        scores[row] = s;
+        const bool h = rule == DASH_RULE_THRESHOLD && !row_protected(row, n, n_first, n_last) && s < tau;
+        halt[row] = h ? 1 : 0;
+        keep = !h;
+    }
+    const unsigned long long m = __ballot(keep);
+    if (lane == 0 && row < n) chunk_counts[row / kChunkRows] = __popcll(m);
+}
+
+__global__ __launch_bounds__(256) void score_only_kernel(const float* __restrict__ partials, int P, int n,
+                                                         int score_kind, float* __restrict__ scores) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row < n) scores[row] = finish_score(partials, P, n, row, score_kind);
+}
+
+// Order-preserving map from fp32 to uint32 (larger float -> larger key; positive NaN above +inf).
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+struct TopkState {
+    uint32_t threshold_key;  // key of the K-th largest candidate score
+    int32_t tie_quota;       // how many rows with exactly that key are kept (earliest rows first)
+};
+
+constexpr int kSelectThreads = 1024;
+
+// TopK selection (Eq. 3): one workgroup finds the key of the k_cand-th largest score among the
+// unprotected rows by four 8-bit radix passes (integer histograms in LDS), then counts, per 64-row
+// chunk, the rows that tie with it, so the flag kernel can keep the earliest ties first.
+__global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
+    const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, TopkState* __restrict__ st,
+    int32_t* __restrict__ tie_counts) {
+    __shared__ int hist[256];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining;
+    const int tid = threadIdx.x;
+    const int lo = min(n_first, n), hi = max(lo, n - n_last);  // candidates are rows [lo, hi)
+    const int n_cand = hi - lo;
+    const int n_prot = n - n_cand;
+    int k_cand = k_keep - n_prot;
+    k_cand = max(0, min(k_cand, n_cand));
+    if (tid == 0) {
+        sh_prefix = 0u;
+        sh_remaining = k_cand;
+    }
+    if (k_cand == 0) {
+        // nothing unprotected survives
+        if (tid == 0) {
+            st->threshold_key = 0xFFFFFFFFu;
+            st->tie_quota = 0;
+        }
+        const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
+        for (int c = tid; c < n_chunks; c += kSelectThreads) tie_counts[c] = 0;
+        return;
+    }
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        for (int b = tid; b < 256; b += kSelectThreads) hist[b] = 0;
+        __syncthreads();
+        const uint32_t prefix = sh_prefix;
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        for (int r = lo + tid; r < hi; r += kSelectThreads) {
+            const uint32_t key = order_key(scores[r]);
+            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFFu], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int remaining = sh_remaining;
+            int b = 255;
+            for (; b > 0; --b) {
+                if (hist[b] >= remaining) break;
+                remaining -= hist[b];
+            }
+            sh_prefix = prefix | ((uint32_t)b << shift);
+            sh_remaining = remaining;
+        }
+        __syncthreads();
+    }
+    const uint32_t T = sh_prefix;
+    if (tid == 0) {
+        st->threshold_key = T;
+        st->tie_quota = sh_remaining;  // >= 1: ties (key == T) still to be kept
+    }
+    // ties per chunk, one wave per chunk
+    const int lane = tid % kWave, wave = tid / kWave;
+    const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
+    for (int c = wave; c < n_chunks; c += kSelectThreads / kWave) {
+        const int row = c * kChunkRows + lane;
+        const bool tie = row >= lo && row < hi && order_key(scores[row]) == T;
+        const unsigned long long m = __ballot(tie);
+        if (lane == 0) tie_counts[c] = __popcll(m);
+    }
+}
+
+// TopK flags: keep protected rows, rows above the threshold key, and the first tie_quota rows equal to it.
+__global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict__ scores, int n, int n_first,
+                                                        int n_last, const TopkState* __restrict__ st,
+                                                        const int32_t* __restrict__ tie_counts,
+                                                        uint8_t* __restrict__ halt,
+                                                        int32_t* __restrict__ chunk_counts) {
+    __shared__ int wave_part[4];
+    const int chunk = blockIdx.x;  // one workgroup per 64-row chunk; wave 0 decides
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    int part = 0;
+    for (int c = tid; c < chunk; c += 256) part += tie_counts[c];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+    if (lane == 0) wave_part[wave] = part;
+    __syncthreads();
+    if (wave != 0) return;
+    const int tie_base = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+    const uint32_t T = st->threshold_key;
+    const int quota = st->tie_quota;
+    const int row = chunk * kChunkRows + lane;
+    bool keep = false, tie = false;
+    if (row < n) {
+        if (row_protected(row, n, n_first, n_last)) {
+            keep = true;
+        } else {
+            const uint32_t key = order_key(scores[row]);
+            keep = key > T;
+            tie = key == T;
+        }
+    }
+    const unsigned long long tie_mask = __ballot(tie);
+    if (tie) keep = tie_base + __popcll(tie_mask & ((1ull << lane) - 1ull)) < quota;
+    if (row < n) halt[row] = keep ? 0 : 1;
+    const unsigned long long m = __ballot(keep);
+    if (lane == 0) chunk_counts[chunk] = __popcll(m);
+}
+
+// Standalone score of Eq. 2 from a stored fp32 delta and x: one wave per row, 16-byte loads.
+template <typename T>
+__global__ __launch_bounds__(256) void score_rows_kernel(const float* __restrict__ delta, const T* __restrict__ x,
+                                                         int n, int d, int kind, float* __restrict__ scores) {
+    const int row = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
+    const int lane = threadIdx.x % kWave;
+    if (row >= n) return;
+    const float* dr = delta + (size_t)row * d;
+    const T* xr = x + (size_t)row * d;
+    float sd = 0.f, sx = 0.f;
+    for (int c = lane * 4; c < d; c += kWave * 4) {  // d % 4 == 0 is checked by the caller
+        const float4 dv = *reinterpret_cast<const float4*>(dr + c);
+        sd += dv.x * dv.x + dv.y * dv.y + dv.z * dv.z + dv.w * dv.w;
+        if (kind == DASH_SCORE_REL) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float xv = to_float(xr[c + e]);
+                sx += xv * xv;
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        sd += __shfl_xor(sd, o);
+        sx += __shfl_xor(sx, o);
+    }
+    if (lane == 0) {
+        const float nd = sqrtf(sd);
+        scores[row] = kind == DASH_SCORE_ABS ? nd : nd / fmaxf(sqrtf(sx), kNormEps);
+    }
+}
+
+size_t decide_workspace_bytes() { return 256; }
+
+dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,
+                                float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
+                                hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    const int blocks = (n + 255) / 256;
+    if (p.rule != DASH_RULE_TOPK) {
+        hipLaunchKernelGGL(score_threshold_kernel, dim3(blocks), dim3(256), 0, s, partials, n_partials, n,
+                           p.score_kind, p.rule, p.tau, p.keep_first_n, p.keep_last_n, scores, halt,
+                           chunk_counts);
+        return launch_status();
+    }
+    int64_t k_keep = p.k_keep;
+    if (k_keep < 0) k_keep = dash_keep_count(n, (double)p.rho, 0, 0, 0);
+    if (k_keep > n) k_keep = n;
+    TopkState* st = reinterpret_cast<TopkState*>(ws);
+    int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
+    const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
+    hipLaunchKernelGGL(score_only_kernel, dim3(blocks), dim3(256), 0, s, partials, n_partials, n,
+                       p.score_kind, scores);
+    hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, p.keep_first_n,
+                       p.keep_last_n, (int)k_keep, st, tie_counts);
+    hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, p.keep_first_n,
+                       p.keep_last_n, st, tie_counts, halt, chunk_counts);
+    return launch_status();
+}
+
+dash_status launch_score_rows(const float* delta, const void* x, int n, int d, int dtype, int kind,
+                              float* scores, hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
+    if (dtype == DASH_BF16)
+        hipLaunchKernelGGL(score_rows_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, delta,
+                           (const __bf16*)x, n, d, kind, scores);
+    else
+        hipLaunchKernelGGL(score_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, delta, (const float*)x,
+                           n, d, kind, scores);
+    return launch_status();
+}
+
+}  // namespace dash

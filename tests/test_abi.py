@@ -1,0 +1,53 @@
+"""The C-ABI library loads on a CPU-only machine and exports every symbol the header declares.
+No compute call is made here; host-only entry points (pure arithmetic) are exercised."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_18103_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dash.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dash_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    syms = declared_symbols()
+    for must in ("dash_attn_layer", "dash_flash_fwd", "dash_wo_residual_rownorm", "dash_score_decide",
+                 "dash_compact", "dash_score_rows", "dash_keep_count", "dash_workspace_bytes"):
+        assert must in syms
+
+
+def test_library_exports_every_declared_symbol():
+    if not os.path.exists(B.LIB_PATH):
+        pytest.fail("libdash.so is not built: run `python -m paper_2604_18103_amd.build`")
+    lib = ctypes.CDLL(B.LIB_PATH)
+    missing = [s for s in declared_symbols() if not hasattr(lib, s)]
+    assert not missing, missing
+
+
+def test_keep_count_matches_both_rules():
+    assert B.keep_count(16384, 0.667) == 5455                       # Eq. 3: floor((1 - rho) T)
+    for n, n_hat in ((8192, 2792), (16384, 5520), (32768, 10976), (65536, 21888), (131072, 43711)):
+        assert B.keep_count(n, 0.667, 64, 32, paper_impl_rounding=True) == n_hat   # App. A, Table 5
+    assert B.keep_count(50, 0.5, 64, 32, paper_impl_rounding=True) == 50
+    assert B.keep_count(10, 1.0) == -1 and B.keep_count(-1, 0.5) == -1
+
+
+def test_host_helpers_validate_params():
+    p = B.make_params(3584, 28, 4, 128)
+    assert B.workspace_bytes(p, 16384) > 16384 * 3584 * 2
+    assert B.norm_partials_per_row(p) > 0
+    # 4 * dh * Hq * n(n+1)/2 + 2 * n * Da * d
+    n = 1000
+    want = 4 * 128 * 28 * n * (n + 1) / 2 + 2 * n * 3584 * 3584
+    assert B.layer_flops(p, n) == want
+    bad = B.make_params(3584, 28, 5, 128)
+    assert B.workspace_bytes(bad, 100) == 0 and B.layer_flops(bad, 100) == 0.0
+    assert B.lib().dash_status_string(-3).decode().startswith("workspace")

@@ -1,0 +1,221 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as ref
+from paper_2604_18103_amd import binding as B
+from paper_2604_18103_amd import inputs as I
+
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+TINY = I.CONFIGS["tiny_f32"]
+QWEN = I.CONFIGS["qwen_8k"]
+LLAMA = I.CONFIGS["llama_128k_40"]
+# a narrow bf16 layer: several query/key tiles and ragged tails at little oracle cost
+NARROW = I.LayerConfig("narrow_bf16", "bf16", 4000, 1333, 512, 4, 2, 128, 0.4, seed=11)
+NARROW64 = I.LayerConfig("narrow_bf16_hd64", "bf16", 2000, 777, 256, 4, 1, 64, 0.5, seed=12)
+
+
+def test_tiny_fp32_config_full():
+    """Benchmark configuration 1 in full: fp32, N=512, hidden 256, 4/1 heads, head_dim 64."""
+    rep, g, o = P.full_parity(TINY, check_delta=True)
+    assert g.n_active_out == o.n_active_out == 256 or rep["band_rows"] > 0
+    print("tiny_f32", rep)
+
+
+@pytest.mark.parametrize("cfg", [NARROW, NARROW64], ids=lambda c: c.name)
+def test_bf16_narrow_layer(cfg):
+    rep, g, o = P.full_parity(cfg, check_delta=True)
+    print(cfg.name, rep)
+
+
+def test_bf16_qwen_shape_ragged():
+    """Qwen2.5-7B layer shape (hidden 3584, 28/4 heads, head_dim 128) at a length that is not a
+    multiple of any tile (query tile 128, key tile 64, GEMM tile 256)."""
+    cfg = I.scaled(QWEN, 715, N=3000)
+    rep, g, o = P.full_parity(cfg)
+    print(cfg.name, rep)
+
+
+def test_bf16_llama_shape_ragged():
+    cfg = I.scaled(LLAMA, 389, N=1000)
+    rep, g, o = P.full_parity(cfg)
+    print(cfg.name, rep)
+
+
+def test_non_causal():
+    cfg = I.scaled(NARROW, 300, N=900, causal=False)
+    P.full_parity(cfg)
+    cfg32 = I.scaled(TINY, 200, N=200, causal=False)
+    P.full_parity(cfg32)
+
+
+def test_absolute_score_kind():
+    P.full_parity(I.scaled(NARROW, 260, N=800), score_kind=B.SCORE_ABS)
+    P.full_parity(I.scaled(TINY, 130, N=130), score_kind=B.SCORE_ABS)
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 128, 129, 257])
+def test_edge_lengths_bf16(n):
+    P.full_parity(I.scaled(NARROW, n, N=4 * n + 3))
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65])
+def test_edge_lengths_fp32(n):
+    P.full_parity(I.scaled(TINY, n, N=n))
+
+
+def test_rule_none_halts_nothing():
+    P.full_parity(I.scaled(NARROW, 200, N=700), rule=B.RULE_NONE)
+
+
+@pytest.mark.parametrize("cfg", [I.scaled(NARROW, 900, N=3000), I.scaled(TINY, 300, N=300)],
+                         ids=["bf16", "f32"])
+def test_topk_rule(cfg):
+    rep, g, o = P.full_parity(cfg, rule=B.RULE_TOPK)
+    assert g.n_active_out == cfg.n - int(np.floor(cfg.halt_frac * cfg.n))
+
+
+def test_protected_prefix_suffix():
+    cfg = I.scaled(NARROW, 500, N=2000, halt_frac=0.7)
+    P.full_parity(cfg, keep_first_n=64, keep_last_n=32)
+    P.full_parity(cfg, rule=B.RULE_TOPK, keep_first_n=64, keep_last_n=32)
+
+
+def _stage_setup(cfg):
+    L = I.make_layer_inputs(cfg)
+    D = P.device_inputs(cfg, L)
+    return L, D
+
+
+def test_all_halt_none_halt_and_empty():
+    cfg = I.scaled(NARROW, 150, N=600)
+    L, D = _stage_setup(cfg)
+    for tau, want in ((0.0, cfg.n), (float("inf"), 0)):
+        params = P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=tau)
+        g = P.run_gpu_layer(cfg, params, D)
+        P.check_self_consistency(g, L["active_idx"], cfg.n)
+        assert g.n_active_out == want
+    # n_active = 0 is a valid no-op that reports zero survivors
+    params = P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=0.5)
+    buf = B.alloc_layer_buffers(params, 0)
+    buf.n_active_out.fill_(77)
+    B.dash_attn_layer(params, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], 0, buf)
+    torch.cuda.synchronize()
+    assert int(buf.n_active_out.item()) == 0
+
+
+def test_zero_output_projection_scores_are_zero():
+    cfg = I.scaled(NARROW, 200, N=500)
+    L, D = _stage_setup(cfg)
+    D["w_o"].zero_()
+    params = P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=1e-6)
+    g = P.run_gpu_layer(cfg, params, D)
+    assert np.all(g.scores == 0.0) and g.n_active_out == 0 and g.halt.all()
+    assert np.array_equal(g.x_next, L["x"])
+
+
+def test_threshold_and_topk_agree_and_runs_are_bit_reproducible():
+    cfg = I.scaled(NARROW, 1000, N=3000)
+    L, D = _stage_setup(cfg)
+    g0 = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_NONE), D)
+    tau, h = I.percentile_tau(g0.scores, 0.35)
+    ga = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=tau), D)
+    gb = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_TOPK, k_keep=cfg.n - h), D)
+    gc = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=tau), D)
+    assert np.array_equal(ga.halt, gb.halt) and ga.n_active_out == gb.n_active_out == cfg.n - h
+    for f in ("x_next", "scores", "halt", "x_compact", "new_active_idx"):
+        assert np.array_equal(getattr(ga, f), getattr(gc, f)), f
+    # rho form of Eq. 3: K = floor((1 - rho) n)
+    gd = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_TOPK, k_keep=-1, rho=0.667), D)
+    assert gd.n_active_out == int(np.floor((1 - np.float64(np.float32(0.667))) * cfg.n))
+
+
+def test_topk_ties_keep_earliest_rows():
+    """Stage-level: hand-made partial sums with many equal scores."""
+    cfg = I.scaled(NARROW, 300, N=300)
+    params = P.params_for(cfg, rule=B.RULE_TOPK, k_keep=120, score_kind=B.SCORE_ABS)
+    Pn = B.norm_partials_per_row(params)
+    n = cfg.n
+    rng = np.random.default_rng(0)
+    vals = rng.integers(1, 6, size=n).astype(np.float32)          # scores sqrt(1..5): heavy ties
+    partials = np.zeros((Pn, n, 2), np.float32)
+    partials[0, :, 0] = vals
+    partials[:, :, 1] = 1.0
+    dp = torch.from_numpy(partials).cuda()
+    scores = torch.empty(n, dtype=torch.float32, device="cuda")
+    halt = torch.empty(n, dtype=torch.uint8, device="cuda")
+    counts = torch.empty((n + 63) // 64, dtype=torch.int32, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    B.dash_score_decide(params, dp, n, scores, halt, counts, ws)
+    torch.cuda.synchronize()
+    want = ref.decide_topk(np.sqrt(vals.astype(np.float64)), 120)
+    assert np.array_equal(halt.cpu().numpy(), want)
+    assert int(counts.sum().item()) == 120
+    np.testing.assert_allclose(scores.cpu().numpy(), np.sqrt(vals), rtol=1e-6)
+
+
+def test_compact_stage_alone_and_score_rows():
+    cfg = I.scaled(NARROW, 1000, N=5000)
+    n, d = cfg.n, cfg.d
+    rng = np.random.default_rng(1)
+    params = P.params_for(cfg)
+    halt_np = (rng.random(n) < 0.6).astype(np.uint8)
+    idx_np = I.make_active_idx(cfg.N, n, 3)
+    xn = torch.randn(n, d, device="cuda").to(torch.bfloat16)
+    halt = torch.from_numpy(halt_np).cuda()
+    idx = torch.from_numpy(idx_np).cuda()
+    xc = torch.empty_like(xn)
+    new_idx = torch.empty(n, dtype=torch.int32, device="cuda")
+    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    B.dash_compact(params, halt, None, idx, xn, n, xc, new_idx, n_out, ws)
+    torch.cuda.synchronize()
+    want_idx, _, want_n = ref.compact(halt_np, idx_np)
+    assert int(n_out.item()) == want_n
+    assert np.array_equal(new_idx[:want_n].cpu().numpy(), want_idx)
+    assert torch.equal(xc[:want_n], xn[torch.from_numpy(halt_np == 0).cuda()])
+    # standalone score of Eq. 2 from a stored delta
+    delta = torch.randn(n, d, device="cuda")
+    s = torch.empty(n, dtype=torch.float32, device="cuda")
+    for kind in (B.SCORE_REL, B.SCORE_ABS):
+        B.dash_score_rows(delta, xn, n, d, B.DASH_BF16, kind, s)
+        torch.cuda.synchronize()
+        want = ref.scores(delta.cpu().numpy(), xn.float().cpu().numpy(), kind=kind)
+        np.testing.assert_allclose(s.cpu().numpy(), want, rtol=2e-6)
+
+
+def test_validate_active_idx_counts_violations():
+    idx = torch.tensor([0, 3, 3, 9, 8, 50], dtype=torch.int32, device="cuda")
+    viol = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.dash_validate_active_idx(idx, 6, 40, viol)
+    torch.cuda.synchronize()
+    assert int(viol.item()) == 3        # repeated 3, descending 8, out-of-range 50
+    good = torch.arange(0, 100, 3, dtype=torch.int32, device="cuda")
+    B.dash_validate_active_idx(good, good.numel(), -1, viol)
+    torch.cuda.synchronize()
+    assert int(viol.item()) == 0
+
+
+def test_invalid_arguments_are_rejected_without_launch():
+    cfg = I.scaled(NARROW, 64, N=64)
+    L, D = _stage_setup(cfg)
+    params = P.params_for(cfg, tau=0.1)
+    buf = B.alloc_layer_buffers(params, cfg.n)
+    small = B.LayerBuffers(**{**buf.__dict__, "workspace": buf.workspace[:256]})
+    with pytest.raises(B.DashError, match="workspace"):
+        B.dash_attn_layer(params, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], cfg.n, small)
+    bad = P.params_for(cfg, tau=0.1)
+    bad.head_dim = 96
+    with pytest.raises(B.DashError, match="unsupported"):
+        B.dash_attn_layer(bad, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], cfg.n, buf)
+    bad2 = P.params_for(cfg, tau=0.1)
+    bad2.n_kv_heads = 3
+    with pytest.raises(B.DashError, match="invalid"):
+        B.dash_attn_layer(bad2, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], cfg.n, buf)
+    mis = D["x"].view(-1)[1:1 + (cfg.n - 1) * cfg.d].view(cfg.n - 1, cfg.d)   # 2-byte offset
+    with pytest.raises(B.DashError, match="invalid"):
+        B.dash_attn_layer(params, mis, D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], cfg.n - 1, buf)
