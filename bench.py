@@ -1,0 +1,156 @@
+#!/usr/bin/env python3
+"""Benchmark of the DASH hot path on one MI355X.
+
+A step = one pass of the whole path (flash attention over the active rows, W_o + residual + row
+norms, score + halting decision, stream compaction) over one batch of synthetic input already
+resident in HBM. Prints ONE JSON line:
+  value     active tokens/s of the whole step (headline workload: Qwen2.5-7B-shaped layer, N=32K, 50% active)
+  roofline  the dominant kernel (flash attention forward) against the dense bf16 MFMA peak, its
+            duration measured with HIP events on the launch stream inside the timed region
+  cpu_baseline  the fp64 CPU oracle timed on a bounded row sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
+HBM_PEAK_GBS = 8000.0
+
+
+def attention_flops(cfg, n):
+    pairs = n * (n + 1) / 2 if cfg.causal else n * n
+    return 4.0 * cfg.head_dim * cfg.n_q_heads * pairs
+
+
+def wo_flops(cfg, n):
+    return 2.0 * n * cfg.D_a * cfg.d
+
+
+def score_compact_bytes(cfg, n, n_kept, partials_per_row, elem):
+    """Algorithmic HBM bytes of score+decision and compaction: per active row the norm partials read,
+    score (4) and mask (1) written, mask (1) and index (4) read; per kept row the hidden row read and
+    written plus the index written."""
+    per_row = 8 * partials_per_row + 4 + 1 + 1 + 4
+    per_kept = 2 * cfg.d * elem + 4
+    return n * per_row + n_kept * per_kept
+
+
+def cpu_baseline(cfg, L, rows_target=3072):
+    """The oracle as it stands on a bounded uniform sample of query rows (cost per row grows with its
+    rank, so a uniform sample gives the mean per-row cost); all keys/values, full layer per row."""
+    import numpy as np
+    from oracle import reference as ref
+    n = cfg.n
+    rng = np.random.default_rng(12345)
+    rows = np.sort(rng.choice(n, size=min(rows_target, n), replace=False))
+    t0 = time.perf_counter()
+    ref.attn_layer(L["x"], L["q"], L["k"], L["v"], L["w_o"], L["active_idx"], causal=cfg.causal, rows=rows)
+    dt = time.perf_counter() - t0
+    return {"value": len(rows) / dt, "unit": "active tokens/s", "cores": ref.num_threads(), "kind": "oracle",
+            "sample": f"{len(rows)} uniformly sampled query rows of the same workload against all "
+                      f"{n} keys/values, full layer per row, {dt:.1f} s; tokens/s = rows / seconds"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="qwen_32k_half",
+                    help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_18103_amd import binding as B
+    from paper_2604_18103_amd import inputs as I
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()  # fail loudly if the HIP library is missing
+    cfg = I.CONFIGS[args.workload]
+    dt_code = B.DASH_BF16 if cfg.dtype == "bf16" else B.DASH_F32
+    elem = 2 if cfg.dtype == "bf16" else 4
+    L = I.make_layer_inputs(cfg)
+    D = {k: B.to_device(L[k], dt_code) for k in ("x", "q", "k", "v", "w_o")}
+    D["active_idx"] = torch.from_numpy(L["active_idx"]).cuda()
+    n = cfg.n
+
+    def params(**kw):
+        return B.make_params(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, dtype=dt_code,
+                             causal=cfg.causal, **kw)
+
+    # tau at the workload's percentile of the active-token scores (one untimed pass, no halting)
+    buf = B.alloc_layer_buffers(params(), n)
+    B.dash_attn_layer(params(rule=B.RULE_NONE), D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], n, buf)
+    torch.cuda.synchronize()
+    tau, h = I.percentile_tau(buf.scores[:n].cpu().numpy(), cfg.halt_frac)
+    p = params(rule=B.RULE_THRESHOLD, tau=tau)
+
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        B.dash_attn_layer(p, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], n, buf)
+    profiles = [B.Profile() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        B.dash_attn_layer(p, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], n, buf, profiles[s])
+    stream.synchronize()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_kept = int(buf.n_active_out.item())
+
+    stage_ms = np.array([pr.read_ms() for pr in profiles])       # [steps, 4]
+    mean_ms = stage_ms.mean(axis=0)
+    ms_per_step = 1e3 * elapsed / args.steps
+    fa_tflops = attention_flops(cfg, n) / (mean_ms[0] * 1e-3) / 1e12
+    wo_tflops = wo_flops(cfg, n) / (mean_ms[1] * 1e-3) / 1e12
+    both_tflops = (attention_flops(cfg, n) + wo_flops(cfg, n)) / ((mean_ms[0] + mean_ms[1]) * 1e-3) / 1e12
+    sc_bytes = score_compact_bytes(cfg, n, n_kept, B.norm_partials_per_row(p), elem)
+    sc_gbs = sc_bytes / ((mean_ms[2] + mean_ms[3]) * 1e-3) / 1e9
+
+    out = {
+        "metric": "active tokens/s, one DASH attention layer step (attention + W_o/residual + score/halting "
+                  "+ compaction), Qwen2.5-7B-shaped layer" if args.workload.startswith("qwen")
+                  else "active tokens/s, one DASH attention layer step",
+        "value": n / (elapsed / args.steps),
+        "unit": "active tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "N": cfg.N, "n_active": n, "hidden": cfg.d,
+                   "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
+                   "causal": cfg.causal, "halt_frac": cfg.halt_frac, "n_kept": n_kept, "tau": tau},
+        "roofline": {"kernel": "flash_fwd_mfma", "bound": "mfma", "achieved": fa_tflops,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": fa_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "stages_ms": dict(zip(B.STAGE_NAMES, [float(v) for v in mean_ms])),
+        "roofline_wo": {"kernel": "gemm_mfma_kernel", "bound": "mfma", "achieved": wo_tflops,
+                        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": wo_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "roofline_attn_plus_wo": {"bound": "mfma", "achieved": both_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                  "unit": "TFLOP/s", "frac": both_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "roofline_score_compact": {"bound": "hbm", "achieved": sc_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "frac": sc_gbs / HBM_PEAK_GBS, "bytes": sc_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, L)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
