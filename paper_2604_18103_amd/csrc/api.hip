@@ -209,7 +209,7 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const vo
     dash_status st = check_params(p);
     if (st != DASH_OK) return st;
     if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
-    if (p->d % 32 != 0) return DASH_ERR_UNSUPPORTED;
+    if (p->d % 64 != 0) return DASH_ERR_UNSUPPORTED;  // K step of the projection GEMM
     if (n < 0) return DASH_ERR_INVALID_ARG;
     if (n == 0) return DASH_OK;
     if (!x || !w_q || !w_k || !w_v || !q || !k || !v || !h_scratch) return DASH_ERR_INVALID_ARG;

@@ -100,26 +100,69 @@ __device__ __forceinline__ s16x4 lds_read_tr16(const __bf16* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
+// Work-item -> (query tile, head) map. Workgroups are handed to the 8 XCDs round-robin
+// (workgroup b runs on XCD b % 8) and each XCD has its own L2, so all workgroups of one XCD are given
+// the same KV head (or as few as possible): its K/V tiles are then fetched into that L2 once and shared
+// by the query heads of the group and by neighbouring query tiles. Heaviest (latest) query tiles first.
+struct FaMap {
+    int xcd_mode;      // 1: XCD-aware, 0: plain
+    int xcds_per_g;    // XCDs serving one KV head (Hkv <= 8)
+    int g_per_xcd;     // KV heads per XCD (Hkv >= 8)
+    int items_per_g;   // n_qtiles * group size
+};
+
+__device__ __forceinline__ bool fa_map_block(const FaMap& mp, int bid, int n_qtiles, int Hq, int Hkv,
+                                             int& qt, int& head) {
+    const int group = Hq / Hkv;
+    if (!mp.xcd_mode) {
+        qt = n_qtiles - 1 - bid / Hq;
+        head = bid % Hq;
+        return true;
+    }
+    const int xcd = bid % 8, slot = bid / 8;
+    int g, idx;
+    if (mp.g_per_xcd == 1) {
+        g = xcd / mp.xcds_per_g;
+        idx = slot * mp.xcds_per_g + xcd % mp.xcds_per_g;
+    } else {
+        g = xcd * mp.g_per_xcd + slot % mp.g_per_xcd;
+        idx = slot / mp.g_per_xcd;
+    }
+    if (idx >= mp.items_per_g) return false;
+    qt = n_qtiles - 1 - idx / group;
+    head = g * group + idx % group;
+    return true;
+}
+
+template <int DH>
+struct FaSmem {
+    static constexpr int KSTR = DH + 8;   // LDS row stride of K (elements): 16 lanes x 16 B hit distinct banks
+    static constexpr int VSTR = DH + 32;  // LDS row stride of V: the 4-row transpose-read groups do
+    static constexpr int K_ELEMS = kFaBN * KSTR;
+    static constexpr int V_ELEMS = kFaBN * VSTR;
+    static constexpr int STAGE_ELEMS = K_ELEMS + V_ELEMS;
+    static constexpr size_t BYTES = 2 * STAGE_ELEMS * sizeof(__bf16);  // two stages
+};
+
 template <int DH>
 __global__ __launch_bounds__(256, 2) void flash_fwd_mfma(const __bf16* __restrict__ q,
                                                          const __bf16* __restrict__ k,
                                                          const __bf16* __restrict__ v,
                                                          const int32_t* __restrict__ pos,
                                                          __bf16* __restrict__ o, int n, int Hq, int Hkv,
-                                                         float scale_log2, int causal, int n_qtiles) {
-    constexpr int KC = DH / 16;      // contraction chunks of Q K^T
-    constexpr int DB = DH / 32;      // 32-wide output blocks of O^T
-    constexpr int KSTR = DH + 8;     // LDS row stride of K (elements): 16 lanes x 16 B hit distinct banks
-    constexpr int VSTR = DH + 32;    // LDS row stride of V: the 4x(2x32 B) transpose-read groups do
+                                                         float scale_log2, int causal, int n_qtiles,
+                                                         FaMap mp) {
+    using SM = FaSmem<DH>;
+    constexpr int KC = DH / 16;  // contraction chunks of Q K^T
+    constexpr int DB = DH / 32;  // 32-wide output blocks of O^T
+    constexpr int KSTR = SM::KSTR, VSTR = SM::VSTR;
     constexpr int VEC_PER_ROW = DH / 8;
     constexpr int LOADS = kFaBN * VEC_PER_ROW / 256;
-    __shared__ __attribute__((aligned(16))) __bf16 Ks[kFaBN * KSTR];
-    __shared__ __attribute__((aligned(16))) __bf16 Vs[kFaBN * VSTR];
-    __shared__ int pos_k[kFaBN];
+    extern __shared__ __attribute__((aligned(16))) unsigned char fa_smem_raw[];
+    __bf16* smem = reinterpret_cast<__bf16*>(fa_smem_raw);
 
-    // heaviest (latest) query tiles first
-    const int qt = n_qtiles - 1 - (int)blockIdx.x / Hq;
-    const int head = (int)blockIdx.x % Hq;
+    int qt, head;
+    if (!fa_map_block(mp, (int)blockIdx.x, n_qtiles, Hq, Hkv, qt, head)) return;  // whole workgroup exits
     const int g = head / (Hq / Hkv);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int j = lane % 32, h = lane / 32;
@@ -145,88 +188,116 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_mfma(const __bf16* __restric
     const int n_tiles = (kv_end + kFaBN - 1) / kFaBN;
     const int wave_kend = causal ? min(n, q0 + 32) : n;  // keys at or beyond this rank are masked for the whole wave
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int key0 = t * kFaBN;
-        __syncthreads();
+    // global -> register -> LDS staging of one K/V tile; thread t moves LOADS 16-byte vectors of each
+    u32x4 kreg[LOADS], vreg[LOADS];
+    const int ld_row = tid / VEC_PER_ROW, ld_c8 = tid % VEC_PER_ROW;
+    constexpr int ROWS_PER_IT = 256 / VEC_PER_ROW;
+    auto load_tile = [&](int key0) {
 #pragma unroll
         for (int it = 0; it < LOADS; ++it) {
-            const int idx = it * 256 + tid;
-            const int row = idx / VEC_PER_ROW, c8 = idx % VEC_PER_ROW;
-            const int krow = min(key0 + row, n - 1);
-            const size_t goff = ((size_t)krow * Hkv + g) * DH + c8 * 8;
-            const u32x4 kv = *reinterpret_cast<const u32x4*>(k + goff);
-            const u32x4 vv = *reinterpret_cast<const u32x4*>(v + goff);
-            *reinterpret_cast<u32x4*>(&Ks[row * KSTR + c8 * 8]) = kv;
-            *reinterpret_cast<u32x4*>(&Vs[row * VSTR + c8 * 8]) = vv;
+            const int krow = min(key0 + ld_row + ROWS_PER_IT * it, n - 1);
+            const size_t goff = ((size_t)krow * Hkv + g) * DH + ld_c8 * 8;
+            kreg[it] = *reinterpret_cast<const u32x4*>(k + goff);
+            vreg[it] = *reinterpret_cast<const u32x4*>(v + goff);
         }
-        if (tid < kFaBN) pos_k[tid] = pos[min(key0 + tid, n - 1)];
-        __syncthreads();
-        if (key0 >= wave_kend) continue;  // wave-uniform: nothing visible to this wave in this tile
+    };
+    auto store_tile = [&](int stage) {
+        __bf16* Ks = smem + stage * SM::STAGE_ELEMS;
+        __bf16* Vs = Ks + SM::K_ELEMS;
+#pragma unroll
+        for (int it = 0; it < LOADS; ++it) {
+            const int row = ld_row + ROWS_PER_IT * it;
+            *reinterpret_cast<u32x4*>(&Ks[row * KSTR + ld_c8 * 8]) = kreg[it];
+            *reinterpret_cast<u32x4*>(&Vs[row * VSTR + ld_c8 * 8]) = vreg[it];
+        }
+    };
 
-        f32x16 S[2];
+    load_tile(0);
+    store_tile(0);
+    // The Q fragments have to be in registers before the loop: if their loads were still in flight at
+    // loop entry, the first MFMAs of every tile would also wait for the next tile's loads (issued later,
+    // returned in order). An empty asm that "uses" them pins the wait here.
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+    for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(Qf[kc]));
+    __syncthreads();
+
+    const int tg = lane / 16, ti = lane % 16;
+    for (int t = 0; t < n_tiles; ++t) {
+        const int key0 = t * kFaBN;
+        const bool has_next = t + 1 < n_tiles;
+        if (has_next) load_tile(key0 + kFaBN);  // in flight while this tile is computed
+        const __bf16* Ks = smem + (t & 1) * SM::STAGE_ELEMS;
+        const __bf16* Vs = Ks + SM::K_ELEMS;
+
+        if (key0 < wave_kend) {  // wave-uniform: otherwise nothing in this tile is visible to this wave
+            f32x16 S[2];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
+            for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + j) * KSTR + 16 * kc + 8 * h]);
-                S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
+                for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
+#pragma unroll
+                for (int kc = 0; kc < KC; ++kc) {
+                    const bf16x8 Kf =
+                        *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + j) * KSTR + 16 * kc + 8 * h]);
+                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
+                }
             }
-        }
-        const bool need_mask = (causal && key0 + kFaBN - 1 > q0) || (key0 + kFaBN > n);
-        if (need_mask) {
+            const bool need_mask = (causal && key0 + kFaBN - 1 > q0) || (key0 + kFaBN > n);
+            if (need_mask) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
+                        const bool bad = (key >= n) || (causal && pos[min(key, n - 1)] > pos_q);
+                        if (bad) S[kb][r] = kMaskedScore;
+                    }
+            }
+            // online softmax in the log2 domain
+            float mx = S[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx * scale_log2);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            float psum = 0.f;
+            bf16x8 Pf[4];
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const int kl = 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
-                    const bool bad = (key0 + kl >= n) || (causal && pos_k[kl] > pos_q);
-                    if (bad) S[kb][r] = kMaskedScore;
+                    const float p = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -m_new));
+                    psum += p;
+                    Pf[2 * kb + r / 8][r % 8] = (__bf16)p;
                 }
-        }
-        // online softmax in the log2 domain
-        float mx = S[0][0];
+            lsum = lsum * alpha + psum;
+            if (__any(alpha != 1.0f)) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx * scale_log2);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        float psum = 0.f;
-        bf16x8 Pf[4];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -m_new));
-                psum += p;
-                Pf[2 * kb + r / 8][r % 8] = (__bf16)p;
+                    for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
             }
-        lsum = lsum * alpha + psum;
-        if (__any(alpha != 1.0f)) {
+            // O^T += V^T P^T
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+            for (int c = 0; c < 4; ++c) {
+                const int kbase = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
 #pragma unroll
-                for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
-        }
-        // O^T += V^T P^T
-        const int tg = lane / 16, ti = lane % 16;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int kbase = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
-                const s16x4 lo = lds_read_tr16(&Vs[kbase * VSTR + col]);
-                const s16x4 hi = lds_read_tr16(&Vs[(kbase + 8) * VSTR + col]);
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 Vf = __builtin_bit_cast(bf16x8, both);
-                Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Vf, Pf[c], Oacc[db], 0, 0, 0);
+                for (int db = 0; db < DB; ++db) {
+                    const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
+                    const s16x4 lo = lds_read_tr16(&Vs[kbase * VSTR + col]);
+                    const s16x4 hi = lds_read_tr16(&Vs[(kbase + 8) * VSTR + col]);
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8 Vf = __builtin_bit_cast(bf16x8, both);
+                    Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Vf, Pf[c], Oacc[db], 0, 0, 0);
+                }
             }
         }
+        // the other stage was last read in iteration t-1, which every wave left through the barrier below
+        if (has_next) store_tile((t + 1) & 1);
+        __syncthreads();
     }
 
     lsum += __shfl_xor(lsum, 32);
@@ -267,15 +338,34 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
                                     (float*)o, scale, s);
     const int n_qtiles = (n + kFaBM - 1) / kFaBM;
     const float scale_log2 = scale * 1.4426950408889634f;
-    const dim3 grid((unsigned)n_qtiles * p.n_q_heads);
-    if (p.head_dim == 64)
-        hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(256), 0, s, (const __bf16*)q, (const __bf16*)k,
-                           (const __bf16*)v, active_idx, (__bf16*)o, n, p.n_q_heads, p.n_kv_heads, scale_log2,
-                           p.causal, n_qtiles);
-    else
-        hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(256), 0, s, (const __bf16*)q, (const __bf16*)k,
-                           (const __bf16*)v, active_idx, (__bf16*)o, n, p.n_q_heads, p.n_kv_heads, scale_log2,
-                           p.causal, n_qtiles);
+    const int Hq = p.n_q_heads, Hkv = p.n_kv_heads, group = Hq / Hkv;
+    FaMap mp{0, 1, 1, n_qtiles * group};
+    unsigned blocks = (unsigned)n_qtiles * Hq;
+    if (Hkv <= 8 && 8 % Hkv == 0) {
+        mp.xcd_mode = 1;
+        mp.xcds_per_g = 8 / Hkv;
+        blocks = 8u * (unsigned)((mp.items_per_g + mp.xcds_per_g - 1) / mp.xcds_per_g);
+    } else if (Hkv % 8 == 0) {
+        mp.xcd_mode = 1;
+        mp.g_per_xcd = Hkv / 8;
+        blocks = 8u * (unsigned)(mp.items_per_g * mp.g_per_xcd);
+    }
+    const dim3 grid(blocks);
+    if (p.head_dim == 64) {
+        static const hipError_t attr64 = hipFuncSetAttribute(
+            (const void*)flash_fwd_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<64>::BYTES);
+        if (attr64 != hipSuccess) return DASH_ERR_HIP;
+        hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(256), FaSmem<64>::BYTES, s, (const __bf16*)q,
+                           (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
+                           p.causal, n_qtiles, mp);
+    } else {
+        static const hipError_t attr128 = hipFuncSetAttribute(
+            (const void*)flash_fwd_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<128>::BYTES);
+        if (attr128 != hipSuccess) return DASH_ERR_HIP;
+        hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(256), FaSmem<128>::BYTES, s, (const __bf16*)q,
+                           (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
+                           p.causal, n_qtiles, mp);
+    }
     return launch_status();
 }
 

@@ -100,10 +100,14 @@ __global__ __launch_bounds__(256) void wo_simple_kernel(const T* __restrict__ A,
 // (256 fp32 accumulator registers per lane). A fragments are 16-byte LDS reads from the [m][k] tile;
 // B fragments come from the natural [k][n] tile through LDS transpose reads.
 // ------------------------------------------------------------------------------------------------
-constexpr int kGM = 256, kGN = 256, kGK = 32;
-constexpr int kGAStr = kGK + 8;     // elements; 80-byte rows: 16 lanes x 16 B land in distinct banks
+constexpr int kGM = 256, kGN = 256, kGK = 64;
+constexpr int kGAStr = kGK + 8;     // elements; 144-byte rows: 16 lanes x 16 B land in distinct banks
 constexpr int kGBStr = kGN + 32;    // elements; 576-byte rows for the transpose reads
 constexpr int kEpiStr = 128 + 4;    // fp32 words per staged epilogue row
+constexpr int kGAElems = kGM * kGAStr, kGBElems = kGK * kGBStr;
+constexpr int kGStageElems = kGAElems + kGBElems;
+constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (147456 B)
+static_assert(kGemmSmemBytes >= 4 * 16 * kEpiStr * sizeof(float), "epilogue staging must fit");
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -114,14 +118,6 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b(const __bf16* p) {
 
 enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1 };
 
-union GemmSmem {
-    struct {
-        __bf16 a[kGM * kGAStr];
-        __bf16 b[kGK * kGBStr];
-    } t;
-    float epi[4][16 * kEpiStr];  // per wave: 16 rows x 128 columns of fp32 accumulators
-};
-
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restrict__ A,
                                                            const __bf16* __restrict__ B, int M, int K, int N,
@@ -129,7 +125,8 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                                                            __bf16* __restrict__ out,  // x_next or C
                                                            float* __restrict__ partials,
                                                            float* __restrict__ delta_dbg, int n_mtiles) {
-    __shared__ __attribute__((aligned(16))) GemmSmem sm;
+    extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
+    __bf16* smem = reinterpret_cast<__bf16*>(gemm_smem_raw);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int j = lane % 32, h = lane / 32;
     const int wm = wave / 2, wn = wave % 2;
@@ -145,16 +142,20 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // global -> register staging: A tile 256x32 (4 x 16 B per thread), B tile 32x256 (4 x 16 B per thread)
-    u32x4 ra[4], rb[4];
-    const int a_row = tid / 4, a_c8 = tid % 4;    // + 64 per step
-    const int b_row = tid / 32, b_c8 = tid % 32;  // + 8 per step
+    // global -> register staging of the next K step: A tile 256x64 and B tile 64x256, 8 x 16 B each per thread
+    constexpr int AL = kGM * kGK / 8 / 256, BL = kGK * kGN / 8 / 256;
+    u32x4 ra[AL], rb[BL];
+    const int a_row = tid / 8, a_c8 = tid % 8;    // + 32 rows per step
+    const int b_row = tid / 32, b_c8 = tid % 32;  // + 8 rows per step
+    const int gn = n0 + b_c8 * 8;
     auto load_tiles = [&](int k0) {
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int gm = min(m0 + a_row + 64 * it, M - 1);
+        for (int it = 0; it < AL; ++it) {
+            const int gm = min(m0 + a_row + 32 * it, M - 1);
             ra[it] = *reinterpret_cast<const u32x4*>(A + (size_t)gm * K + k0 + a_c8 * 8);
-            const int gn = n0 + b_c8 * 8;
+        }
+#pragma unroll
+        for (int it = 0; it < BL; ++it) {
             const int gk = k0 + b_row + 8 * it;
             if (gn < N)
                 rb[it] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gn);
@@ -162,35 +163,40 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                 rb[it] = u32x4{0u, 0u, 0u, 0u};
         }
     };
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](int stage) {
+        __bf16* sa = smem + stage * kGStageElems;
+        __bf16* sb = sa + kGAElems;
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            *reinterpret_cast<u32x4*>(&sm.t.a[(a_row + 64 * it) * kGAStr + a_c8 * 8]) = ra[it];
-            *reinterpret_cast<u32x4*>(&sm.t.b[(b_row + 8 * it) * kGBStr + b_c8 * 8]) = rb[it];
-        }
+        for (int it = 0; it < AL; ++it)
+            *reinterpret_cast<u32x4*>(&sa[(a_row + 32 * it) * kGAStr + a_c8 * 8]) = ra[it];
+#pragma unroll
+        for (int it = 0; it < BL; ++it)
+            *reinterpret_cast<u32x4*>(&sb[(b_row + 8 * it) * kGBStr + b_c8 * 8]) = rb[it];
     };
 
     const int tg = lane / 16, ti = lane % 16;
+    const int n_ksteps = K / kGK;
     load_tiles(0);
-    for (int k0 = 0; k0 < K; k0 += kGK) {
-        __syncthreads();
-        store_tiles();
-        __syncthreads();
-        if (k0 + kGK < K) load_tiles(k0 + kGK);
+    store_tiles(0);
+    __syncthreads();
+    for (int kt = 0; kt < n_ksteps; ++kt) {
+        const bool has_next = kt + 1 < n_ksteps;
+        if (has_next) load_tiles((kt + 1) * kGK);  // in flight while this step is computed
+        const __bf16* sa = smem + (kt & 1) * kGStageElems;
+        const __bf16* sb = sa + kGAElems;
 #pragma unroll
         for (int ks = 0; ks < kGK / 16; ++ks) {
             bf16x8 Af[4], Bf[4];
 #pragma unroll
             for (int a = 0; a < 4; ++a)
-                Af[a] = *reinterpret_cast<const bf16x8*>(
-                    &sm.t.a[(wm * 128 + 32 * a + j) * kGAStr + 16 * ks + 8 * h]);
+                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[(wm * 128 + 32 * a + j) * kGAStr + 16 * ks + 8 * h]);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*128 + 32b + 16*(tg%2) + 4*(ti%4)
                 const int krow = 16 * ks + 8 * (tg / 2) + ti / 4;
                 const int col = wn * 128 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
-                const s16x4 lo = lds_read_tr16_b(&sm.t.b[krow * kGBStr + col]);
-                const s16x4 hi = lds_read_tr16_b(&sm.t.b[(krow + 4) * kGBStr + col]);
+                const s16x4 lo = lds_read_tr16_b(&sb[krow * kGBStr + col]);
+                const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGBStr + col]);
                 Bf[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
 #pragma unroll
@@ -199,12 +205,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                 for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[a], Bf[b], acc[a][b], 0, 0, 0);
         }
+        // the other stage was last read in step kt-1, which every wave left through the barrier below
+        if (has_next) store_tiles((kt + 1) & 1);
+        __syncthreads();
     }
-    __syncthreads();  // all waves are done with the operand tiles; LDS is reused for the epilogue
+    // all waves are past the last barrier: the operand stages are free and are reused by the epilogue
 
     // Epilogue: stage 16 rows x 128 columns of this wave's accumulators in LDS, then every lane handles
     // 8 consecutive columns of one row: 16-byte x loads, 16-byte x_next stores, in-row sums over 16 lanes.
-    float* stage = sm.epi[wave];
+    float* stage = reinterpret_cast<float*>(gemm_smem_raw) + wave * 16 * kEpiStr;
     const int e_row = lane / 16, e_c8 = lane % 16;
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
@@ -302,7 +311,11 @@ int norm_partials_per_row(int d, int dtype) {
 static dash_status launch_gemm_store(const __bf16* A, const __bf16* B, int M, int K, int N, __bf16* C,
                                      hipStream_t s) {
     const int mt = (M + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN;
-    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_STORE>), dim3(mt * nt), dim3(256), 0, s, A, B, M, K, N,
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_STORE>,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                        (int)kGemmSmemBytes);
+    if (attr != hipSuccess) return DASH_ERR_HIP;
+    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_STORE>), dim3(mt * nt), dim3(256), kGemmSmemBytes, s, A, B, M, K, N,
                        (const __bf16*)nullptr, C, (float*)nullptr, (float*)nullptr, mt);
     return launch_status();
 }
@@ -319,7 +332,11 @@ dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o
         return launch_status();
     }
     const int mt = (n + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN;
-    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_RESIDUAL_NORM>), dim3(mt * nt), dim3(256), 0, s,
+    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_RESIDUAL_NORM>,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                        (int)kGemmSmemBytes);
+    if (attr != hipSuccess) return DASH_ERR_HIP;
+    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_RESIDUAL_NORM>), dim3(mt * nt), dim3(256), kGemmSmemBytes, s,
                        (const __bf16*)o, (const __bf16*)w_o, n, K, N, (const __bf16*)x, (__bf16*)x_next,
                        partials, delta_dbg, mt);
     return launch_status();
