@@ -75,8 +75,8 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 // ------------------------------------------------------------------------------------------------
 // MFMA kernel.
 //
-// Workgroup = 4 waves = 128 query rows of one head; wave w owns rows 32w..32w+31. Keys/values come in
-// tiles of 64, staged through LDS in their natural [key][dim] layout.
+// Workgroup = 8 waves = 256 query rows of one head; wave w owns rows 32w..32w+31. Keys/values come in
+// tiles of 64, staged through LDS in their natural [key][dim] layout, two stages each.
 //
 //   S^T = K Q^T   (A = K fragment from LDS, B = Q fragment held in registers for the whole kernel):
 //         with the 32x32 accumulator layout each lane then holds 16 scores of ONE query per 32-key
@@ -84,11 +84,22 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 //   O^T += V^T P^T (A = V^T fragment via LDS transpose reads, B = P^T): the accumulator registers of
 //         S^T, converted to bf16, already ARE the B fragment - no shuffle, no LDS round trip.
 //
+// Per score the softmax costs about as many VALU cycles as the two MFMAs cost matrix-core cycles, and a
+// wave that runs them back to back leaves each pipe idle half the time. So the eight waves form two
+// groups (waves 0-3 and 4-7; wave w and w+4 share a SIMD) that alternate roles, separated by workgroup
+// barriers: in every phase one group issues only MFMAs (O += P V of the previous tile, then S = K Q^T
+// of the next), the other only the softmax VALU work of its current tile, and the SIMD co-executes them.
+//     phase 2t   : group 0  PV(t-1), S(t)      group 1  softmax(t-1)
+//     phase 2t+1 : group 0  softmax(t)         group 1  PV(t-1), S(t)
+// K(t) and V(t-1) are read in phases 2t and 2t+1; K(t+1) and V(t) are fetched into registers at the
+// start of phase 2t and written to the other LDS stages at the end of phase 2t+1.
+//
 // MFMA 32x32x16 operand layout (lane l, i = l%32, h = l/32): A holds row i, k-slots 8h..8h+7;
 // B holds column i, k-slots 8h..8h+7; D register r holds row 8*(r/4) + 4h + r%4 of column i.
 // ------------------------------------------------------------------------------------------------
-constexpr int kFaBM = 128;  // query rows per workgroup
+constexpr int kFaBM = 256;  // query rows per workgroup
 constexpr int kFaBN = 64;   // keys per tile
+constexpr int kFaThreads = 512;
 constexpr float kMaskedScore = -1.0e30f;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -140,32 +151,43 @@ struct FaSmem {
     static constexpr int VSTR = DH + 32;  // LDS row stride of V: the 4-row transpose-read groups do
     static constexpr int K_ELEMS = kFaBN * KSTR;
     static constexpr int V_ELEMS = kFaBN * VSTR;
-    static constexpr int STAGE_ELEMS = K_ELEMS + V_ELEMS;
-    static constexpr size_t BYTES = 2 * STAGE_ELEMS * sizeof(__bf16);  // two stages
+    static constexpr size_t BYTES = 2 * (K_ELEMS + V_ELEMS) * sizeof(__bf16);  // two stages of each
 };
 
 template <int DH>
-__global__ __launch_bounds__(256, 2) void flash_fwd_mfma(const __bf16* __restrict__ q,
-                                                         const __bf16* __restrict__ k,
-                                                         const __bf16* __restrict__ v,
-                                                         const int32_t* __restrict__ pos,
-                                                         __bf16* __restrict__ o, int n, int Hq, int Hkv,
-                                                         float scale_log2, int causal, int n_qtiles,
-                                                         FaMap mp) {
+__global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __restrict__ q,
+                                                                const __bf16* __restrict__ k,
+                                                                const __bf16* __restrict__ v,
+                                                                const int32_t* __restrict__ pos,
+                                                                __bf16* __restrict__ o, int n, int Hq,
+                                                                int Hkv, float scale_log2, int causal,
+                                                                int n_qtiles, FaMap mp) {
     using SM = FaSmem<DH>;
     constexpr int KC = DH / 16;  // contraction chunks of Q K^T
     constexpr int DB = DH / 32;  // 32-wide output blocks of O^T
     constexpr int KSTR = SM::KSTR, VSTR = SM::VSTR;
     constexpr int VEC_PER_ROW = DH / 8;
     constexpr int LOADS = kFaBN * VEC_PER_ROW / 256;
+    constexpr int ROWS_PER_IT = 256 / VEC_PER_ROW;
     extern __shared__ __attribute__((aligned(16))) unsigned char fa_smem_raw[];
-    __bf16* smem = reinterpret_cast<__bf16*>(fa_smem_raw);
+    __bf16* Kst = reinterpret_cast<__bf16*>(fa_smem_raw);  // two K stages, then two V stages
+    __bf16* Vst = Kst + 2 * SM::K_ELEMS;
+    __shared__ __attribute__((aligned(16))) int pos_blk[kFaBM];  // original positions of this workgroup's rows
 
     int qt, head;
     if (!fa_map_block(mp, (int)blockIdx.x, n_qtiles, Hq, Hkv, qt, head)) return;  // whole workgroup exits
     const int g = head / (Hq / Hkv);
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    // the wave index is made provably uniform: the role branches below must be scalar branches, never
+    // exec-masked regions (MFMA ignores the exec mask)
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+#ifdef DASH_FA_GRP_ALT
+    const int grp = wave & 1;
+#else
+    const int grp = wave >> 2;
+#endif
     const int j = lane % 32, h = lane / 32;
+    const int tg = lane / 16, ti = lane % 16;
     const int q0 = qt * kFaBM + wave * 32;
     const int qrow = q0 + j;
     const int qrow_c = min(qrow, n - 1);
@@ -182,123 +204,190 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_mfma(const __bf16* __restric
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) Oacc[db][r] = 0.f;
+    f32x16 S[2];
+    uint32_t Pw[4][4];  // P^T of the previous tile as packed bf16 pairs: Pw[c] is the B fragment of key chunk c
     float m = kMaskedScore, lsum = 0.f;
 
     const int kv_end = causal ? min(n, qt * kFaBM + kFaBM) : n;
     const int n_tiles = (kv_end + kFaBN - 1) / kFaBN;
     const int wave_kend = causal ? min(n, q0 + 32) : n;  // keys at or beyond this rank are masked for the whole wave
 
-    // global -> register -> LDS staging of one K/V tile; thread t moves LOADS 16-byte vectors of each
-    u32x4 kreg[LOADS], vreg[LOADS];
-    const int ld_row = tid / VEC_PER_ROW, ld_c8 = tid % VEC_PER_ROW;
-    constexpr int ROWS_PER_IT = 256 / VEC_PER_ROW;
-    auto load_tile = [&](int key0) {
+    // global -> register -> LDS staging: the 256 threads of group 0 copy the K tiles, those of group 1 the
+    // V tiles, LOADS 16-byte vectors per thread and tile
+    u32x4 stg[LOADS];
+#ifdef DASH_FA_GRP_ALT
+    const int gtid = (wave >> 1) * kWave + lane;
+#else
+    const int gtid = tid & 255;
+#endif
+    const int ld_row = gtid / VEC_PER_ROW, ld_c8 = gtid % VEC_PER_ROW;
+    const size_t row_stride = (size_t)Hkv * DH;
+    const __bf16* ld_base = (grp == 0 ? k : v) + (size_t)g * DH + ld_c8 * 8;
+    auto load_rows = [&](int key0) {
 #pragma unroll
         for (int it = 0; it < LOADS; ++it) {
-            const int krow = min(key0 + ld_row + ROWS_PER_IT * it, n - 1);
-            const size_t goff = ((size_t)krow * Hkv + g) * DH + ld_c8 * 8;
-            kreg[it] = *reinterpret_cast<const u32x4*>(k + goff);
-            vreg[it] = *reinterpret_cast<const u32x4*>(v + goff);
+            const int row = min(key0 + ld_row + ROWS_PER_IT * it, n - 1);
+            stg[it] = *reinterpret_cast<const u32x4*>(ld_base + (size_t)row * row_stride);
         }
     };
-    auto store_tile = [&](int stage) {
-        __bf16* Ks = smem + stage * SM::STAGE_ELEMS;
-        __bf16* Vs = Ks + SM::K_ELEMS;
+    auto store_rows = [&](__bf16* stage, int stride) {
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it) {
-            const int row = ld_row + ROWS_PER_IT * it;
-            *reinterpret_cast<u32x4*>(&Ks[row * KSTR + ld_c8 * 8]) = kreg[it];
-            *reinterpret_cast<u32x4*>(&Vs[row * VSTR + ld_c8 * 8]) = vreg[it];
+        for (int it = 0; it < LOADS; ++it)
+            *reinterpret_cast<u32x4*>(&stage[(ld_row + ROWS_PER_IT * it) * stride + ld_c8 * 8]) = stg[it];
+    };
+
+    // O^T += V^T(t) P^T(t): A = V^T fragment by transpose reads, B = packed P
+    auto pv_mfma = [&](int t) {
+        const __bf16* Vs = Vst + (t & 1) * SM::V_ELEMS;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int kbase_row = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
+            const u32x4 pw = {Pw[c][0], Pw[c][1], Pw[c][2], Pw[c][3]};
+            const bf16x8 Pf = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
+                const s16x4 lo = lds_read_tr16(&Vs[kbase_row * VSTR + col]);
+                const s16x4 hi = lds_read_tr16(&Vs[(kbase_row + 8) * VSTR + col]);
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), Pf,
+                                                                   Oacc[db], 0, 0, 0);
+            }
+        }
+        // issue order: operand reads run four MFMAs ahead, so no MFMA waits for a read issued just before it
+        constexpr int NM = 4 * DB;
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+        for (int i = 0; i < NM - 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    };
+    // S^T = K(t) Q^T
+    auto qk_mfma = [&](int t) {
+        const __bf16* Ks = Kst + (t & 1) * SM::K_ELEMS;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
+#pragma unroll
+            for (int kc = 0; kc < KC; ++kc) {
+                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + j) * KSTR + 16 * kc + 8 * h]);
+                S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
+            }
+        }
+        constexpr int NM = 2 * KC;
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < NM - 4; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    };
+    auto tile_active = [&](int t) { return t >= 0 && t < n_tiles && t * kFaBN < wave_kend; };  // wave-uniform
+
+    // matrix-core phase of tile t: finish the previous tile's P V, start this tile's scores
+    auto mfma_phase = [&](int t) {
+        if (tile_active(t - 1)) pv_mfma(t - 1);
+        if (tile_active(t)) qk_mfma(t);
+    };
+    // VALU phase of tile t: online softmax in the log2 domain on S, leaves packed P in Pw
+    auto valu_phase = [&](int t) {
+        if (!tile_active(t)) return;
+        const int key0 = t * kFaBN;
+        // Causal masks are only ever needed on tiles that lie inside the workgroup's own row range, whose
+        // original positions sit in LDS (pos_blk); masking compares positions, not ranks.
+        const bool diag = causal && key0 + kFaBN - 1 > q0;  // wave-uniform
+        if (diag || key0 + kFaBN > n) {
+            const int kl0 = key0 - qt * kFaBM;  // >= 0 whenever diag holds
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int rg = 0; rg < 4; ++rg) {
+                    const int kl = 32 * kb + 8 * rg + 4 * h;  // four consecutive keys of this lane
+                    int4 kp = make_int4(0, 0, 0, 0);
+                    if (diag) kp = *reinterpret_cast<const int4*>(&pos_blk[kl0 + kl]);
+                    const int kpe[4] = {kp.x, kp.y, kp.z, kp.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const bool bad = (key0 + kl + e >= n) || (diag && kpe[e] > pos_q);
+                        S[kb][4 * rg + e] = bad ? kMaskedScore : S[kb][4 * rg + e];
+                    }
+                }
+        }
+        float mx = fmaxf(S[0][0], S[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, S[0][r]), S[1][r]);  // v_max3_f32
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m, mx * scale_log2);
+        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+        m = m_new;
+        // the row sum is taken over the bf16-rounded probabilities, the same values the P V product uses
+        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+        float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -m_new));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], scale_log2, -m_new));
+                const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
+                if (r & 2)
+                    ps1 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps1, false);
+                else
+                    ps0 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps0, false);
+                Pw[2 * kb + r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, pk);
+            }
+        lsum = lsum * alpha + (ps0 + ps1);
+        if (__any(alpha != 1.0f)) {
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
         }
     };
 
-    load_tile(0);
-    store_tile(0);
+    if (grp == 0) {
+        load_rows(0);
+        store_rows(Kst, KSTR);  // K(0)
+    } else {
+        load_rows(0);  // V(0), written to LDS at the end of interval 1
+    }
+    if (tid < kFaBM) pos_blk[tid] = pos[min(qt * kFaBM + tid, n - 1)];
     // The Q fragments have to be in registers before the loop: if their loads were still in flight at
-    // loop entry, the first MFMAs of every tile would also wait for the next tile's loads (issued later,
+    // loop entry, the first MFMAs of every tile would also wait for the staging loads (issued later,
     // returned in order). An empty asm that "uses" them pins the wait here.
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(Qf[kc]));
     __syncthreads();
 
-    const int tg = lane / 16, ti = lane % 16;
-    for (int t = 0; t < n_tiles; ++t) {
-        const int key0 = t * kFaBN;
-        const bool has_next = t + 1 < n_tiles;
-        if (has_next) load_tile(key0 + kFaBN);  // in flight while this tile is computed
-        const __bf16* Ks = smem + (t & 1) * SM::STAGE_ELEMS;
-        const __bf16* Vs = Ks + SM::K_ELEMS;
-
-        if (key0 < wave_kend) {  // wave-uniform: otherwise nothing in this tile is visible to this wave
-            f32x16 S[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
-#pragma unroll
-                for (int kc = 0; kc < KC; ++kc) {
-                    const bf16x8 Kf =
-                        *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + j) * KSTR + 16 * kc + 8 * h]);
-                    S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
-                }
-            }
-            const bool need_mask = (causal && key0 + kFaBN - 1 > q0) || (key0 + kFaBN > n);
-            if (need_mask) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + 32 * kb + 8 * (r / 4) + 4 * h + (r % 4);
-                        const bool bad = (key >= n) || (causal && pos[min(key, n - 1)] > pos_q);
-                        if (bad) S[kb][r] = kMaskedScore;
-                    }
-            }
-            // online softmax in the log2 domain
-            float mx = S[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[kb][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx * scale_log2);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-            m = m_new;
-            float psum = 0.f;
-            bf16x8 Pf[4];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -m_new));
-                    psum += p;
-                    Pf[2 * kb + r / 8][r % 8] = (__bf16)p;
-                }
-            lsum = lsum * alpha + psum;
-            if (__any(alpha != 1.0f)) {
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
-            }
-            // O^T += V^T P^T
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const int kbase = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
-#pragma unroll
-                for (int db = 0; db < DB; ++db) {
-                    const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
-                    const s16x4 lo = lds_read_tr16(&Vs[kbase * VSTR + col]);
-                    const s16x4 hi = lds_read_tr16(&Vs[(kbase + 8) * VSTR + col]);
-                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    const bf16x8 Vf = __builtin_bit_cast(bf16x8, both);
-                    Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Vf, Pf[c], Oacc[db], 0, 0, 0);
-                }
-            }
-        }
-        // the other stage was last read in iteration t-1, which every wave left through the barrier below
-        if (has_next) store_tile((t + 1) & 1);
-        __syncthreads();
+    // Both groups run the same loop (matrix-core phase, barrier, VALU phase, barrier); group 1 is skewed
+    // by one barrier interval, so in every interval one group is in its MFMA phase and the other in its
+    // softmax phase. Interval 2t: group 0 MFMA(t), group 1 softmax(t-1); interval 2t+1: group 0
+    // softmax(t), group 1 MFMA(t). K(t+1) and V(t) must be in LDS by the end of interval 2t+1; their
+    // stages were last read in interval 2t-1. Every wave passes the same number of barriers:
+    // waves whose rows cannot see a tile skip its work, not its barriers. The extra round t = n_tiles
+    // only drains P V of the final tile.
+    // barrier that orders LDS traffic only: the staging loads in flight must not be waited for here
+    auto lds_barrier = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+    if (grp == 1) lds_barrier();
+    for (int t = 0; t <= n_tiles; ++t) {
+        if (grp == 0 && t + 1 < n_tiles) load_rows((t + 1) * kFaBN);       // K(t+1), start of interval 2t
+        mfma_phase(t);
+        if (grp == 1 && t < n_tiles) store_rows(Vst + (t & 1) * SM::V_ELEMS, VSTR);  // V(t), end of interval 2t+1
+        lds_barrier();
+        if (grp == 1 && t + 1 < n_tiles) load_rows((t + 1) * kFaBN);       // V(t+1), start of interval 2t+2
+        valu_phase(t);
+        if (grp == 0 && t + 1 < n_tiles) store_rows(Kst + ((t + 1) & 1) * SM::K_ELEMS, KSTR);  // end of interval 2t+1
+        lds_barrier();
     }
+    if (grp == 0) lds_barrier();
 
     lsum += __shfl_xor(lsum, 32);
     const float inv = 1.0f / lsum;
@@ -355,14 +444,14 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
         static const hipError_t attr64 = hipFuncSetAttribute(
             (const void*)flash_fwd_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<64>::BYTES);
         if (attr64 != hipSuccess) return DASH_ERR_HIP;
-        hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(256), FaSmem<64>::BYTES, s, (const __bf16*)q,
+        hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(kFaThreads), FaSmem<64>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
                            p.causal, n_qtiles, mp);
     } else {
         static const hipError_t attr128 = hipFuncSetAttribute(
             (const void*)flash_fwd_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<128>::BYTES);
         if (attr128 != hipSuccess) return DASH_ERR_HIP;
-        hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(256), FaSmem<128>::BYTES, s, (const __bf16*)q,
+        hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(kFaThreads), FaSmem<128>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
                            p.causal, n_qtiles, mp);
     }
