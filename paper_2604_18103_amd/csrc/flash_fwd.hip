@@ -101,6 +101,7 @@ constexpr int kFaBM = 256;  // query rows per workgroup
 constexpr int kFaBN = 64;   // keys per tile
 constexpr int kFaThreads = 512;
 constexpr float kMaskedScore = -1.0e30f;
+constexpr float kRowSumLimit = 1048576.0f;  // a lane's 32-key partial row sum above this moves the softmax reference
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -181,11 +182,7 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     // the wave index is made provably uniform: the role branches below must be scalar branches, never
     // exec-masked regions (MFMA ignores the exec mask)
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-#ifdef DASH_FA_GRP_ALT
-    const int grp = wave & 1;
-#else
     const int grp = wave >> 2;
-#endif
     const int j = lane % 32, h = lane / 32;
     const int tg = lane / 16, ti = lane % 16;
     const int q0 = qt * kFaBM + wave * 32;
@@ -215,19 +212,24 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     // global -> register -> LDS staging: the 256 threads of group 0 copy the K tiles, those of group 1 the
     // V tiles, LOADS 16-byte vectors per thread and tile
     u32x4 stg[LOADS];
-#ifdef DASH_FA_GRP_ALT
-    const int gtid = (wave >> 1) * kWave + lane;
-#else
     const int gtid = tid & 255;
-#endif
     const int ld_row = gtid / VEC_PER_ROW, ld_c8 = gtid % VEC_PER_ROW;
-    const size_t row_stride = (size_t)Hkv * DH;
-    const __bf16* ld_base = (grp == 0 ? k : v) + (size_t)g * DH + ld_c8 * 8;
-    auto load_rows = [&](int key0) {
+    // 32-bit byte offsets (the launcher checks the tensors are below 2 GiB), advanced by one tile per
+    // load and clamped to the last row, which keeps the address arithmetic to two VALU ops per vector
+    const uint32_t row_bytes = (uint32_t)Hkv * DH * 2u;
+    const uint32_t col_bytes = ((uint32_t)g * DH + ld_c8 * 8) * 2u;
+    const uint32_t last_off = (uint32_t)(n - 1) * row_bytes + col_bytes;
+    const uint32_t tile_bytes = (uint32_t)kFaBN * row_bytes;
+    uint32_t ld_off[LOADS];
+#pragma unroll
+    for (int it = 0; it < LOADS; ++it)
+        ld_off[it] = min((uint32_t)(ld_row + ROWS_PER_IT * it) * row_bytes + col_bytes, last_off);
+    const char* ld_base = reinterpret_cast<const char*>(grp == 0 ? k : v);
+    auto load_next_tile = [&]() {  // tiles are fetched strictly in order: 0, 1, 2, ...
 #pragma unroll
         for (int it = 0; it < LOADS; ++it) {
-            const int row = min(key0 + ld_row + ROWS_PER_IT * it, n - 1);
-            stg[it] = *reinterpret_cast<const u32x4*>(ld_base + (size_t)row * row_stride);
+            stg[it] = *reinterpret_cast<const u32x4*>(ld_base + ld_off[it]);
+            ld_off[it] = min(ld_off[it] + tile_bytes, last_off);
         }
     };
     auto store_rows = [&](__bf16* stage, int stride) {
@@ -290,10 +292,32 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
 
     // matrix-core phase of tile t: finish the previous tile's P V, start this tile's scores
     auto mfma_phase = [&](int t) {
+        // While a wave is in its matrix-core phase it gets issue priority over the wave of the other group
+        // on the same SIMD: an MFMA is issued as soon as the pipe frees, VALU work fills the gaps.
+        __builtin_amdgcn_s_setprio(3);
         if (tile_active(t - 1)) pv_mfma(t - 1);
         if (tile_active(t)) qk_mfma(t);
+        __builtin_amdgcn_s_setprio(0);
     };
-    // VALU phase of tile t: online softmax in the log2 domain on S, leaves packed P in Pw
+    // probabilities of the tile in S relative to `ref`, packed to bf16 pairs into Pw; returns this lane's
+    // part of the row sum. fp32 adds on four chains: a bf16 dot2 would halve the instruction count, but it
+    // executes on the matrix pipe and (measured) serialises with the other group's MFMAs.
+    auto exp_pack = [&](float ref) {
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; r += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -ref));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], scale_log2, -ref));
+                ps[(r / 2) % 4] += p0;
+                ps[(r / 2 + 2) % 4] += p1;
+                const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
+                Pw[2 * kb + r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, pk);
+            }
+        return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+    };
+    // VALU phase of tile t: softmax numerators in the log2 domain on S, leaves packed P in Pw
     auto valu_phase = [&](int t) {
         if (!tile_active(t)) return;
         const int key0 = t * kFaBN;
@@ -317,43 +341,43 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
                     }
                 }
         }
-        float mx = fmaxf(S[0][0], S[1][0]);
+        // Probabilities are taken against a reference m that is NOT the running maximum: any reference
+        // gives the same O / sum, it only has to keep exp2 in range. The common tile therefore computes
+        // no row maximum at all: it exponentiates against the current reference and looks at the row
+        // sums; only if a sum is not a modest finite number (a score far above the reference, or the
+        // first tile, where the reference is still -1e30) the reference moves to the true running
+        // maximum, what was accumulated is rescaled, and the tile's probabilities are redone.
+        float psum = exp_pack(m);
+        if (__any(!(psum < kRowSumLimit))) {
+            float c0 = fmaxf(S[0][0], S[1][0]), c1 = fmaxf(S[0][1], S[1][1]);
+            float c2 = fmaxf(S[0][2], S[1][2]), c3 = fmaxf(S[0][3], S[1][3]);
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, S[0][r]), S[1][r]);  // v_max3_f32
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx * scale_log2);
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        m = m_new;
-        // the row sum is taken over the bf16-rounded probabilities, the same values the P V product uses
-        const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-        float ps0 = 0.f, ps1 = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int r = 0; r < 16; r += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -m_new));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], scale_log2, -m_new));
-                const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
-                if (r & 2)
-                    ps1 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps1, false);
-                else
-                    ps0 = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, ps0, false);
-                Pw[2 * kb + r / 8][(r % 8) / 2] = __builtin_bit_cast(uint32_t, pk);
+            for (int r = 4; r < 16; r += 4) {
+                c0 = fmaxf(fmaxf(c0, S[0][r]), S[1][r]);  // v_max3_f32
+                c1 = fmaxf(fmaxf(c1, S[0][r + 1]), S[1][r + 1]);
+                c2 = fmaxf(fmaxf(c2, S[0][r + 2]), S[1][r + 2]);
+                c3 = fmaxf(fmaxf(c3, S[0][r + 3]), S[1][r + 3]);
             }
-        lsum = lsum * alpha + (ps0 + ps1);
-        if (__any(alpha != 1.0f)) {
+            float mx = fmaxf(fmaxf(c0, c1), fmaxf(c2, c3));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx * scale_log2);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            m = m_new;
+            lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
+            psum = exp_pack(m);
         }
+        lsum += psum;
     };
 
     if (grp == 0) {
-        load_rows(0);
+        load_next_tile();
         store_rows(Kst, KSTR);  // K(0)
     } else {
-        load_rows(0);  // V(0), written to LDS at the end of interval 1
+        load_next_tile();  // V(0), written to LDS at the end of interval 1
     }
     if (tid < kFaBM) pos_blk[tid] = pos[min(qt * kFaBM + tid, n - 1)];
     // The Q fragments have to be in registers before the loop: if their loads were still in flight at
@@ -378,11 +402,11 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     };
     if (grp == 1) lds_barrier();
     for (int t = 0; t <= n_tiles; ++t) {
-        if (grp == 0 && t + 1 < n_tiles) load_rows((t + 1) * kFaBN);       // K(t+1), start of interval 2t
+        if (grp == 0 && t + 1 < n_tiles) load_next_tile();  // K(t+1), start of interval 2t
         mfma_phase(t);
         if (grp == 1 && t < n_tiles) store_rows(Vst + (t & 1) * SM::V_ELEMS, VSTR);  // V(t), end of interval 2t+1
         lds_barrier();
-        if (grp == 1 && t + 1 < n_tiles) load_rows((t + 1) * kFaBN);       // V(t+1), start of interval 2t+2
+        if (grp == 1 && t + 1 < n_tiles) load_next_tile();  // V(t+1), start of interval 2t+2
         valu_phase(t);
         if (grp == 0 && t + 1 < n_tiles) store_rows(Kst + ((t + 1) & 1) * SM::K_ELEMS, KSTR);  // end of interval 2t+1
         lds_barrier();
@@ -425,6 +449,8 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
     if (p.dtype == DASH_F32)
         return launch_simple<float>(p, (const float*)q, (const float*)k, (const float*)v, active_idx, n,
                                     (float*)o, scale, s);
+    // the MFMA kernel addresses K and V with 32-bit byte offsets
+    if ((size_t)n * p.n_kv_heads * p.head_dim * 2 >= (size_t)1 << 31) return DASH_ERR_UNSUPPORTED;
     const int n_qtiles = (n + kFaBM - 1) / kFaBM;
     const float scale_log2 = scale * 1.4426950408889634f;
     const int Hq = p.n_q_heads, Hkv = p.n_kv_heads, group = Hq / Hkv;
