@@ -107,7 +107,7 @@ constexpr int kEpiStr = 128 + 4;    // fp32 words per staged epilogue row
 constexpr int kGAElems = kGM * kGAStr, kGBElems = kGK * kGBStr;
 constexpr int kGStageElems = kGAElems + kGBElems;
 constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (147456 B)
-static_assert(kGemmSmemBytes >= 4 * 16 * kEpiStr * sizeof(float), "epilogue staging must fit");
+static_assert(kGemmSmemBytes >= 4 * 32 * kEpiStr * sizeof(float), "epilogue staging must fit");
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
     u32x4 ra[AL], rb[BL];
     const int a_row = tid / 8, a_c8 = tid % 8;    // + 32 rows per step
     const int b_row = tid / 32, b_c8 = tid % 32;  // + 8 rows per step
-    const int gn = n0 + b_c8 * 8;
+    const int gn = min(n0 + b_c8 * 8, N - 8);  // columns beyond N are computed on clamped data and never stored
     auto load_tiles = [&](int k0) {
 #pragma unroll
         for (int it = 0; it < AL; ++it) {
@@ -157,10 +157,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
 #pragma unroll
         for (int it = 0; it < BL; ++it) {
             const int gk = k0 + b_row + 8 * it;
-            if (gn < N)
-                rb[it] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gn);
-            else
-                rb[it] = u32x4{0u, 0u, 0u, 0u};
+            rb[it] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gn);
         }
     };
     auto store_tiles = [&](int stage) {
@@ -176,13 +173,15 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
 
     const int tg = lane / 16, ti = lane % 16;
     const int n_ksteps = K / kGK;
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
-    for (int kt = 0; kt < n_ksteps; ++kt) {
-        const bool has_next = kt + 1 < n_ksteps;
-        if (has_next) load_tiles((kt + 1) * kGK);  // in flight while this step is computed
-        const __bf16* sa = smem + (kt & 1) * kGStageElems;
+    // barrier that orders LDS traffic only: the global loads of the next step must stay in flight across it
+    auto lds_barrier = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    };
+    // 64 MFMAs of one K step on the operand stage `st`
+    auto compute_step = [&](int st) {
+        const __bf16* sa = smem + st * kGStageElems;
         const __bf16* sb = sa + kGAElems;
 #pragma unroll
         for (int ks = 0; ks < kGK / 16; ++ks) {
@@ -205,75 +204,111 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                 for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[a], Bf[b], acc[a][b], 0, 0, 0);
         }
+    };
+    load_tiles(0);
+    store_tiles(0);
+    __syncthreads();
+    // Steady state: one straight-line block per K step with its issue order pinned - the fragment reads of
+    // the first 16-wide slice up front, then every MFMA paired with one read for a later slice; the
+    // global loads of the next step ride along the first MFMAs and its LDS writes along the last ones,
+    // by which time the loads have had about 1500 cycles to land.
+    for (int kt = 0; kt + 1 < n_ksteps; ++kt) {
+        load_tiles((kt + 1) * kGK);
+        compute_step(kt & 1);
         // the other stage was last read in step kt-1, which every wave left through the barrier below
-        if (has_next) store_tiles((kt + 1) & 1);
-        __syncthreads();
+        store_tiles((kt + 1) & 1);
+        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 20; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+        }
+        lds_barrier();
     }
+    compute_step((n_ksteps - 1) & 1);
+    __syncthreads();
     // all waves are past the last barrier: the operand stages are free and are reused by the epilogue
 
-    // Epilogue: stage 16 rows x 128 columns of this wave's accumulators in LDS, then every lane handles
-    // 8 consecutive columns of one row: 16-byte x loads, 16-byte x_next stores, in-row sums over 16 lanes.
-    float* stage = reinterpret_cast<float*>(gemm_smem_raw) + wave * 16 * kEpiStr;
+    // Epilogue, per 32-row block of the wave's 128x128 tile: stage the fp32 accumulators in LDS, then every
+    // lane handles 8 consecutive columns of one row - 16-byte x loads, 16-byte x_next stores, in-row sums
+    // over 16 lanes. The x vectors of the next block are fetched before the current one is processed.
+    float* stage = reinterpret_cast<float*>(gemm_smem_raw) + wave * 32 * kEpiStr;
     const int e_row = lane / 16, e_c8 = lane % 16;
+    const int gn_e = n0 + wn * 128 + 8 * e_c8;
+    const bool col_ok = gn_e < N;
+    bf16x8 xv[2][8];
+    auto fetch_x = [&](int a, bf16x8* dst) {
+#pragma unroll
+        for (int step = 0; step < 8; ++step) {
+            const int gm = min(m0 + wm * 128 + 32 * a + 4 * step + e_row, M - 1);
+            dst[step] = *reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + min(gn_e, N - 8));
+        }
+    };
+    if (EPI == EPI_RESIDUAL_NORM) fetch_x(0, xv[0]);
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
+        if (EPI == EPI_RESIDUAL_NORM && a + 1 < 4) fetch_x(a + 1, xv[(a + 1) & 1]);
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int b = 0; b < 4; ++b)
+            for (int r = 0; r < 16; ++r)  // accumulator register r: local row 8*(r/4) + 4h + r%4, column j
+                stage[(8 * (r / 4) + 4 * h + r % 4) * kEpiStr + 32 * b + j] = acc[a][b][r];
+        __syncthreads();  // every wave runs the same epilogue schedule, so the barrier is uniform
 #pragma unroll
-                for (int rr = 0; rr < 8; ++rr) {
-                    const int r = 8 * half + rr;  // accumulator register: local row 8*(rr/4) + 4h + rr%4
-                    stage[(8 * (rr / 4) + 4 * h + rr % 4) * kEpiStr + 32 * b + j] = acc[a][b][r];
-                }
-            __syncthreads();  // every wave runs the same epilogue schedule, so the barrier is uniform
-#pragma unroll
-            for (int step = 0; step < 4; ++step) {
-                const int lr = 4 * step + e_row;
-                const int gm = m0 + wm * 128 + 32 * a + 16 * half + lr;
-                const int gn = n0 + wn * 128 + 8 * e_c8;
-                const f32x4 d0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8]);
-                const f32x4 d1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8 + 4]);
-                float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-                const bool ok = gm < M && gn < N;
+        for (int step = 0; step < 8; ++step) {
+            const int lr = 4 * step + e_row;
+            const int gm = m0 + wm * 128 + 32 * a + lr;
+            const f32x4 d0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8]);
+            const f32x4 d1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8 + 4]);
+            const float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+            const bool ok = gm < M && col_ok;
+            if (EPI == EPI_RESIDUAL_NORM) {
                 float sd = 0.f, sx = 0.f;
-                if (EPI == EPI_RESIDUAL_NORM) {
-                    if (ok) {
-                        const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + gn);
-                        bf16x8 ov;
+                if (ok) {
+                    const bf16x8 xr = xv[a & 1][step];
+                    bf16x8 ov;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const float xf = (float)xv[e];
-                            ov[e] = (__bf16)(xf + dv[e]);
-                            sd = fmaf(dv[e], dv[e], sd);
-                            sx = fmaf(xf, xf, sx);
-                        }
-                        *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn) = ov;
-                        if (delta_dbg) {
-                            *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn) = d0;
-                            *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn + 4) = d1;
-                        }
+                    for (int e = 0; e < 8; ++e) {
+                        const float xf = (float)xr[e];
+                        ov[e] = (__bf16)(xf + dv[e]);
+                        sd = fmaf(dv[e], dv[e], sd);
+                        sx = fmaf(xf, xf, sx);
                     }
-#pragma unroll
-                    for (int off = 8; off > 0; off >>= 1) {
-                        sd += __shfl_xor(sd, off);
-                        sx += __shfl_xor(sx, off);
-                    }
-                    if (e_c8 == 0 && gm < M) {
-                        const int p = tile_n * 2 + wn;
-                        *reinterpret_cast<float2*>(partials + ((size_t)p * M + gm) * 2) = make_float2(sd, sx);
-                    }
-                } else {
-                    if (ok) {
-                        bf16x8 ov;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) ov[e] = (__bf16)dv[e];
-                        *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn) = ov;
+                    *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn_e) = ov;
+                    if (delta_dbg) {
+                        *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn_e) = d0;
+                        *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn_e + 4) = d1;
                     }
                 }
+#pragma unroll
+                for (int off = 8; off > 0; off >>= 1) {
+                    sd += __shfl_xor(sd, off);
+                    sx += __shfl_xor(sx, off);
+                }
+                if (e_c8 == 0 && gm < M) {
+                    const int p = tile_n * 2 + wn;
+                    *reinterpret_cast<float2*>(partials + ((size_t)p * M + gm) * 2) = make_float2(sd, sx);
+                }
+            } else if (ok) {
+                bf16x8 ov;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ov[e] = (__bf16)dv[e];
+                *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn_e) = ov;
             }
-            __syncthreads();
         }
+        __syncthreads();
     }
 }
 
