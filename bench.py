@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a
+# copy kernel of known size (see profiles/hbm_traffic_and_pipe_counters_qwen_32k_half.md); offline
+# measurements, so only the workload they were taken on has one.
+FLASH_TRAFFIC_BYTES = {"qwen_32k_half": 388e6 + 117e6}
 
 
 def attention_flops(cfg, n):
@@ -67,6 +71,9 @@ def main():
     ap.add_argument("--workload", default="qwen_32k_half",
                     help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run device-to-device copies of this many MiB (a plain copy kernel of known "
+                         "size, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -114,6 +121,13 @@ def main():
     elapsed = time.perf_counter() - t0
     n_kept = int(buf.n_active_out.item())
 
+    if args.copy_calibration_mib > 0:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     stage_ms = np.array([pr.read_ms() for pr in profiles])       # [steps, 4]
     mean_ms = stage_ms.mean(axis=0)
     ms_per_step = 1e3 * elapsed / args.steps
@@ -137,7 +151,10 @@ def main():
                    "causal": cfg.causal, "halt_frac": cfg.halt_frac, "n_kept": n_kept, "tau": tau},
         "roofline": {"kernel": "flash_fwd_mfma", "bound": "mfma", "achieved": fa_tflops,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": fa_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "frac": fa_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": FLASH_TRAFFIC_BYTES.get(cfg.name),
+                     "algorithmic_flops_per_launch": attention_flops(cfg, n),
+                     "kernel_ms": float(mean_ms[0])},
         "stages_ms": dict(zip(B.STAGE_NAMES, [float(v) for v in mean_ms])),
         "roofline_wo": {"kernel": "gemm_mfma_kernel", "bound": "mfma", "achieved": wo_tflops,
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",

@@ -123,7 +123,7 @@ dash_status dash_flash_fwd(const dash_layer_params *params, const void *q, const
                            const int32_t *active_idx, int32_t n_active, void *o, void *hip_stream);
 
 /* Stage 1. delta = o @ w_o; x_next = x + delta (Sec. 3.1, Alg. 1 step 6); per-row partial sums of
- * delta^2 and x^2 taken from the fp32 accumulators: norm_partials [n, P, 2] fp32 with
+ * delta^2 and x^2 taken from the fp32 accumulators: norm_partials [P, n, 2] fp32 (P-major) with
  * P = dash_norm_partials_per_row(params). delta_dbg NULL or fp32 [n,d].
  * workspace: device scratch of dash_workspace_bytes(params, n) (only part is used). */
 dash_status dash_wo_residual_rownorm(const dash_layer_params *params, const void *o, const void *w_o,
@@ -133,7 +133,8 @@ dash_status dash_wo_residual_rownorm(const dash_layer_params *params, const void
 
 /* Stage 2. scores (Eq. 2) from the partials, then the decision (Eq. 3 / threshold).
  * chunk_keep_counts: device int32 [ceil(n/64)], kept rows per 64-row chunk, consumed by dash_compact.
- * workspace: device scratch, >= 8 KiB (TopK selection state). */
+ * workspace: device scratch, needed for TOPK only: >= 256 + 4*ceil(n/64) bytes, 16-byte aligned
+ * (selection state and tie counts). */
 dash_status dash_score_decide(const dash_layer_params *params, const float *norm_partials, int32_t n,
                               float *scores, uint8_t *halt_mask, int32_t *chunk_keep_counts,
                               void *workspace, size_t workspace_bytes, void *hip_stream);

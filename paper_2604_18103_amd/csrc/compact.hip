@@ -61,14 +61,27 @@ __global__ __launch_bounds__(kCompactThreads) void compact_kernel(
         if (chunk == (int)gridDim.x - 1 && lane == 0) *n_out = base + cnt;
     }
 
-    // gather: wave w copies kept rows w, w+4, ...; lanes stride over this split's 16-byte vectors
+    // gather: a wave copies its kept rows four at a time (four independent 16-byte loads per lane in
+    // flight before the first store); lanes stride over this split's vectors
     const int v0 = blockIdx.y * vecs_per_split;
     const int v1 = min(row_vecs, v0 + vecs_per_split);
-    for (int r = wave; r < cnt; r += kCompactWaves) {
-        const uint4* src = x_next + (size_t)kept_rows[r] * row_vecs;
-        uint4* dst = x_compact + (size_t)(base + r) * row_vecs;
-#pragma unroll 4
-        for (int c = v0 + lane; c < v1; c += kWave) dst[c] = src[c];
+    constexpr int R = 4;
+    for (int r0 = wave * R; r0 < cnt; r0 += kCompactWaves * R) {
+        const uint4* src[R];
+        uint4* dst[R];
+#pragma unroll
+        for (int i = 0; i < R; ++i) {
+            const int r = min(r0 + i, cnt - 1);  // a clamped duplicate rewrites the same bytes
+            src[i] = x_next + (size_t)kept_rows[r] * row_vecs;
+            dst[i] = x_compact + (size_t)(base + r) * row_vecs;
+        }
+        for (int c = v0 + lane; c < v1; c += kWave) {
+            uint4 val[R];
+#pragma unroll
+            for (int i = 0; i < R; ++i) val[i] = src[i][c];
+#pragma unroll
+            for (int i = 0; i < R; ++i) dst[i][c] = val[i];
+        }
     }
 }
 
@@ -101,12 +114,12 @@ dash_status launch_compact(const uint8_t* halt, const int32_t* chunk_counts, con
     }
     const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
     const int row_vecs = row_bytes / 16;
-    // enough workgroups to fill 256 CUs several times over, but at least one wave-width of vectors each
+    // column splits of whole wave-widths (64 vectors), enough workgroups to fill 256 CUs several times over
+    const int wave_cols = (row_vecs + kWave - 1) / kWave;
     int splits = (2048 + n_chunks - 1) / n_chunks;
-    const int max_splits = (row_vecs + kWave - 1) / kWave;
-    if (splits > max_splits) splits = max_splits;
+    if (splits > wave_cols) splits = wave_cols;
     if (splits < 1) splits = 1;
-    const int vecs_per_split = (row_vecs + splits - 1) / splits;
+    const int vecs_per_split = ((wave_cols + splits - 1) / splits) * kWave;
     splits = (row_vecs + vecs_per_split - 1) / vecs_per_split;
     hipLaunchKernelGGL(compact_kernel, dim3(n_chunks, splits), dim3(kCompactThreads), 0, s, halt,
                        chunk_counts, active_idx, (const uint4*)x_next, n, row_vecs, vecs_per_split,

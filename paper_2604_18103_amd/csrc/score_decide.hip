@@ -8,41 +8,67 @@
 
 namespace dash {
 
-__device__ __forceinline__ float finish_score(const float* __restrict__ partials, int P, int n, int row,
-                                              int score_kind) {
+// Sum of the P partial pairs of one row, taken by the four threads (row, q = 0..3) of a 256-thread
+// workgroup that covers 64 rows: thread q adds partials q, q+4, ... in order, then the four sums are
+// added in order q = 0..3 through LDS. Fixed order, so the score is bit-reproducible.
+__device__ __forceinline__ float2 row_sums_256(const float* __restrict__ partials, int P, int n, int row_base,
+                                               float2 (*red)[kChunkRows]) {
+    const int r = threadIdx.x % kChunkRows, qd = threadIdx.x / kChunkRows;
+    const int row = row_base + r;
     float sd = 0.f, sx = 0.f;
-    for (int p = 0; p < P; ++p) {
-        const float2 v = *reinterpret_cast<const float2*>(partials + ((size_t)p * n + row) * 2);
-        sd += v.x;
-        sx += v.y;
+    if (row < n) {
+#pragma unroll 4
+        for (int p = qd; p < P; p += 4) {
+            const float2 v = *reinterpret_cast<const float2*>(partials + ((size_t)p * n + row) * 2);
+            sd += v.x;
+            sx += v.y;
+        }
     }
-    const float nd = sqrtf(sd);
-    if (score_kind == DASH_SCORE_ABS) return nd;
-    return nd / fmaxf(sqrtf(sx), kNormEps);
+    red[qd][r] = make_float2(sd, sx);
+    __syncthreads();
+    float2 t = red[0][r];
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        t.x += red[k][r].x;
+        t.y += red[k][r].y;
+    }
+    return t;  // valid in every thread; callers use the copy of wave 0
 }
 
-// rule NONE / THRESHOLD: score, flag and the chunk's kept count in one pass. One wave per 64-row chunk.
+__device__ __forceinline__ float score_from_sums(float2 t, int score_kind) {
+    const float nd = sqrtf(t.x);
+    if (score_kind == DASH_SCORE_ABS) return nd;
+    return nd / fmaxf(sqrtf(t.y), kNormEps);
+}
+
+// rule NONE / THRESHOLD: score, flag and the chunk's kept count in one pass. One workgroup per 64-row chunk.
 __global__ __launch_bounds__(256) void score_threshold_kernel(
     const float* __restrict__ partials, int P, int n, int score_kind, int rule, float tau, int n_first,
     int n_last, float* __restrict__ scores, uint8_t* __restrict__ halt, int32_t* __restrict__ chunk_counts) {
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    const int lane = threadIdx.x % kWave;
+    __shared__ float2 red[4][kChunkRows];
+    const int row_base = blockIdx.x * kChunkRows;
+    const float2 t = row_sums_256(partials, P, n, row_base, red);
+    if (threadIdx.x >= kChunkRows) return;
+    const int row = row_base + threadIdx.x;
     bool keep = false;
     if (row < n) {
-        const float s = finish_score(partials, P, n, row, score_kind);
+        const float s = score_from_sums(t, score_kind);
         scores[row] = s;
         const bool h = rule == DASH_RULE_THRESHOLD && !row_protected(row, n, n_first, n_last) && s < tau;
         halt[row] = h ? 1 : 0;
         keep = !h;
     }
     const unsigned long long m = __ballot(keep);
-    if (lane == 0 && row < n) chunk_counts[row / kChunkRows] = __popcll(m);
+    if (threadIdx.x == 0) chunk_counts[blockIdx.x] = __popcll(m);
 }
 
 __global__ __launch_bounds__(256) void score_only_kernel(const float* __restrict__ partials, int P, int n,
                                                          int score_kind, float* __restrict__ scores) {
-    const int row = blockIdx.x * blockDim.x + threadIdx.x;
-    if (row < n) scores[row] = finish_score(partials, P, n, row, score_kind);
+    __shared__ float2 red[4][kChunkRows];
+    const int row_base = blockIdx.x * kChunkRows;
+    const float2 t = row_sums_256(partials, P, n, row_base, red);
+    const int row = row_base + threadIdx.x;
+    if (threadIdx.x < kChunkRows && row < n) scores[row] = score_from_sums(t, score_kind);
 }
 
 // Order-preserving map from fp32 to uint32 (larger float -> larger key; positive NaN above +inf).
@@ -201,7 +227,7 @@ dash_status launch_score_decide(const dash_layer_params& p, const float* partial
                                 float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
                                 hipStream_t s) {
     if (n == 0) return DASH_OK;
-    const int blocks = (n + 255) / 256;
+    const int blocks = (n + kChunkRows - 1) / kChunkRows;
     if (p.rule != DASH_RULE_TOPK) {
         hipLaunchKernelGGL(score_threshold_kernel, dim3(blocks), dim3(256), 0, s, partials, n_partials, n,
                            p.score_kind, p.rule, p.tau, p.keep_first_n, p.keep_last_n, scores, halt,
