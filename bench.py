@@ -63,6 +63,53 @@ def cpu_baseline(cfg, L, rows_target=3072):
                       f"{n} keys/values, full layer per row, {dt:.1f} s; tokens/s = rows / seconds"}
 
 
+def run_chain_bench(args, cfg, n_layers=8):
+    """Eight attention-only layers (RMSNorm + q/k/v projections + the layer step), halting the lowest 20 %
+    of the active scores after every layer (on-device TopK), the compacted output of one layer feeding the
+    next. A step = the whole chain; per-layer n_active and time are reported."""
+    import numpy as np
+    import torch
+    from paper_2604_18103_amd import binding as B
+    from paper_2604_18103_amd import chain as CH
+    from paper_2604_18103_amd import inputs as I
+
+    weights = [{k: B.to_device(v, B.DASH_BF16) for k, v in I.make_projection_weights(cfg, l).items()}
+               for l in range(n_layers)]
+    x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)
+    idx0 = torch.from_numpy(I.make_active_idx(cfg.N, cfg.n, cfg.seed)).cuda()
+    state = CH.alloc_chain(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n)
+    for _ in range(max(1, args.warmup)):
+        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    layers = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, time_layers=True)
+    flops = 0.0
+    for r in layers:
+        n = r["n_in"]
+        r["flops"] = (attention_flops(cfg, n) + wo_flops(cfg, n)
+                      + 2.0 * n * cfg.d * (cfg.D_a + 2 * cfg.n_kv_heads * cfg.head_dim))
+        r["tflops"] = r["flops"] / (r["ms"] * 1e-3) / 1e12
+        flops += r["flops"]
+    tokens = sum(r["n_in"] for r in layers)
+    ms = 1e3 * elapsed / args.steps
+    print(json.dumps({
+        "metric": "active tokens/s over a chain of 8 attention-only layers with halting after every layer, "
+                  "Qwen2.5-7B-shaped, N=32768",
+        "value": tokens / (elapsed / args.steps), "unit": "active tokens/s (sum over layers)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "N": cfg.N, "layers": n_layers, "halt_frac_per_layer": cfg.halt_frac,
+                   "hidden": cfg.d, "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim},
+        "chain_tflops": flops / (ms * 1e-3) / 1e12,
+        "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "layers": layers}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +137,9 @@ def main():
         sys.exit(1)
     B.lib()  # fail loudly if the HIP library is missing
     cfg = I.CONFIGS[args.workload]
+    if args.workload == "qwen_32k_chain":
+        run_chain_bench(args, cfg)
+        return
     dt_code = B.DASH_BF16 if cfg.dtype == "bf16" else B.DASH_F32
     elem = 2 if cfg.dtype == "bf16" else 4
     L = I.make_layer_inputs(cfg)

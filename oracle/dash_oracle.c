@@ -15,6 +15,8 @@
  *                          textbook causal softmax attention with grouped KV
  *                          heads, causality decided on ORIGINAL token positions
  *                          (Sec. 3.4: blocks run on the compacted active sequence)
+ *   - rmsnorm            : the LN of Eq. 1 as unit-gain RMS normalisation (front end
+ *                          of a layer chain; sits before the path proper)
  *   - project            : the output projection that completes U (Sec. 3.1:
  *                          U is the attention output before the residual add)
  *   - residual           : H~ = H + U                  (Sec. 3.1, Alg. 1 step 6)
@@ -138,6 +140,22 @@ int dash_oracle_project(const double *O, const double *w_o, int64_t m, int32_t D
             const double *wr = w_o + (size_t)a * d;
             for (int32_t c = 0; c < d; ++c) di[c] += oa * wr[c];
         }
+    }
+    return 0;
+}
+
+/*
+ * Front end of a layer in a chain: the LN of Eq. 1 taken as RMS normalisation with unit gain,
+ *   h_t = x_t / sqrt(mean_c(x_tc^2) + eps).
+ * (The q/k/v projections that follow are plain products: dash_oracle_project.)
+ */
+int dash_oracle_rmsnorm(const double *x, int64_t m, int32_t d, double eps, double *out) {
+    if (!x || !out || m < 0 || d <= 0 || eps < 0.0) return -1;
+    for (int64_t i = 0; i < m; ++i) {
+        double ss = 0.0;
+        for (int32_t c = 0; c < d; ++c) ss += x[(size_t)i * d + c] * x[(size_t)i * d + c];
+        const double inv = 1.0 / sqrt(ss / (double)d + eps);
+        for (int32_t c = 0; c < d; ++c) out[(size_t)i * d + c] = x[(size_t)i * d + c] * inv;
     }
     return 0;
 }

@@ -45,6 +45,7 @@ def _load():
                                                C.c_int32, C.c_int32, C.c_double, i64p, C.c_int64, dp]
     lib.dash_oracle_project.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_residual.argtypes = [dp, dp, C.c_int64, C.c_int32, dp]
+    lib.dash_oracle_rmsnorm.argtypes = [dp, C.c_int64, C.c_int32, C.c_double, dp]
     lib.dash_oracle_scores.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_decide_threshold.argtypes = [dp, C.c_int64, C.c_double, C.c_int64, C.c_int64, u8p]
     lib.dash_oracle_decide_topk.argtypes = [dp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, u8p]
@@ -109,6 +110,25 @@ def project(O, w_o) -> np.ndarray:
     _check(_load().dash_oracle_project(_ptr(O, C.c_double), _ptr(w_o, C.c_double), m, Da, d,
                                        _ptr(delta, C.c_double)), "project")
     return delta
+
+
+def rmsnorm(x, eps=1e-6) -> np.ndarray:
+    """LN of Eq. 1 as unit-gain RMS normalisation: x / sqrt(mean(x^2) + eps) per row."""
+    x = _f64(x)
+    m, d = x.shape
+    out = np.empty_like(x)
+    _check(_load().dash_oracle_rmsnorm(_ptr(x, C.c_double), m, d, float(eps), _ptr(out, C.c_double)), "rmsnorm")
+    return out
+
+
+def rmsnorm_qkv(x, w_q, w_k, w_v, n_q_heads, n_kv_heads, head_dim, eps=1e-6):
+    """Front end of a layer in a chain: h = rmsnorm(x); q, k, v = h @ W_q, h @ W_k, h @ W_v."""
+    h = rmsnorm(x, eps)
+    n = h.shape[0]
+    q = project(h, w_q).reshape(n, n_q_heads, head_dim)
+    k = project(h, w_k).reshape(n, n_kv_heads, head_dim)
+    v = project(h, w_v).reshape(n, n_kv_heads, head_dim)
+    return q, k, v
 
 
 def residual(x, delta) -> np.ndarray:

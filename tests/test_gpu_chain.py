@@ -1,0 +1,85 @@
+"""Front end (RMSNorm + q/k/v projections) and the layer chain with halting after every layer."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as ref
+from paper_2604_18103_amd import binding as B
+from paper_2604_18103_amd import chain as CH
+from paper_2604_18103_amd import inputs as I
+
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+CFG = I.LayerConfig("chain_small", "bf16", 900, 900, 512, 4, 2, 128, 0.2, seed=31)
+
+
+def _dev(a):
+    return B.to_device(a, B.DASH_BF16)
+
+
+def test_rmsnorm_qkv_matches_oracle():
+    cfg = I.scaled(CFG, 333, N=333)
+    x = I.make_hidden(cfg)
+    W = I.make_projection_weights(cfg, 0)
+    p = P.params_for(cfg)
+    n = cfg.n
+    q = torch.empty((n, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    k = torch.empty((n, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    h = torch.empty((n, cfg.d), dtype=torch.bfloat16, device="cuda")
+    B.dash_rmsnorm_qkv(p, _dev(x), _dev(W["w_q"]), _dev(W["w_k"]), _dev(W["w_v"]), n, q, k, v, h)
+    torch.cuda.synchronize()
+    oq, ok, ov = ref.rmsnorm_qkv(x, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    for got, want in ((q, oq), (k, ok), (v, ov)):
+        err = P.row_rel_err(got.float().cpu().numpy().reshape(n, -1), want.reshape(n, -1))
+        assert err.max() <= 2e-2, err.max()
+    herr = P.row_rel_err(h.float().cpu().numpy(), ref.rmsnorm(x))
+    assert herr.max() <= 8e-3          # one bf16 rounding
+
+
+def test_chain_teacher_forced_against_oracle():
+    """Four layers; at every layer the oracle is run on the GPU's actual layer input and active set, so
+    band flips cannot compound. Also: the active set only shrinks, halted tokens never return, TopK keeps
+    exactly k_keep."""
+    cfg = CFG
+    n_layers = 4
+    weights_np = [I.make_projection_weights(cfg, l) for l in range(n_layers)]
+    weights = [{k: _dev(v) for k, v in W.items()} for W in weights_np]
+    state = CH.alloc_chain(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n)
+    x0 = _dev(I.make_hidden(cfg))
+    idx0 = torch.from_numpy(I.make_active_idx(cfg.N, cfg.n, cfg.seed)).cuda()
+    seen = {"prev": set(idx0.cpu().numpy().tolist()), "halted": set(), "band": 0}
+
+    def check(l, x, idx, n, q, k, v, buf):
+        f = lambda t: t.float().cpu().numpy()
+        xs, qs, ks, vs = f(x[:n]), f(q[:n]), f(k[:n]), f(v[:n])
+        idx_np = idx[:n].cpu().numpy()
+        W = weights_np[l]
+        # front end of this layer
+        oq, ok, ov = ref.rmsnorm_qkv(xs, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+        assert P.row_rel_err(qs.reshape(n, -1), oq.reshape(n, -1)).max() <= 2e-2
+        assert P.row_rel_err(vs.reshape(n, -1), ov.reshape(n, -1)).max() <= 2e-2
+        # the path proper, on the values the GPU kernels actually consumed
+        k_keep = n - int(cfg.halt_frac * n)
+        o = ref.attn_layer(xs, qs, ks, vs, W["w_o"], idx_np, rule=ref.RULE_TOPK, k_keep=k_keep)
+        n_out = int(buf.n_active_out.item())
+        g = P.GpuResult(f(buf.x_next[:n]), buf.scores[:n].cpu().numpy(), buf.halt_mask[:n].cpu().numpy(),
+                        f(buf.x_compact[:n_out]), buf.new_active_idx[:n_out].cpu().numpy(), n_out, None)
+        P.check_self_consistency(g, idx_np, n)
+        assert n_out == k_keep == o.n_active_out
+        assert P.row_rel_err(g.x_next, o.x_next).max() <= P.X_TOL["bf16"]
+        thr = np.sort(o.scores)[::-1][k_keep - 1]
+        band = np.abs(o.scores - thr) <= P.BAND_REL * thr
+        assert np.array_equal(g.halt[~band], o.halt[~band])
+        seen["band"] += int(band.sum())
+        cur = set(g.new_active_idx.tolist())
+        assert cur <= seen["prev"] and not (cur & seen["halted"])
+        seen["halted"] |= seen["prev"] - cur
+        seen["prev"] = cur
+
+    recs = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, on_layer=check)
+    ns = [r["n_in"] for r in recs] + [recs[-1]["n_out"]]
+    assert all(a > b for a, b in zip(ns, ns[1:])), ns
+    print("chain n_active:", ns, "band rows:", seen["band"])

@@ -333,3 +333,34 @@ def test_eq3_keep_count_is_floor():
     assert ref.keep_count(100, 0.0) == 100
     # paper's quoted fixed active length floor((1-rho)T) in Sec. 3.4 for rho = 0.667, T = 16384
     assert ref.keep_count(16384, 0.667) == math.floor((1 - 0.667) * 16384)
+
+
+# ---------------------------------------------------------------- chain front end (LN of Eq. 1)
+
+def test_rmsnorm_closed_forms():
+    eps = 1e-6
+    x = np.array([[3.0, 4.0], [2.0, 2.0], [0.0, 0.0], [-5.0, 0.0]])
+    got = ref.rmsnorm(x, eps)
+    np.testing.assert_allclose(got[0], np.array([3.0, 4.0]) / math.sqrt(12.5 + eps), rtol=1e-15)
+    np.testing.assert_allclose(got[1], np.array([2.0, 2.0]) / math.sqrt(4.0 + eps), rtol=1e-15)
+    assert np.all(got[2] == 0.0)
+    np.testing.assert_allclose(got[3], np.array([-5.0, 0.0]) / math.sqrt(12.5 + eps), rtol=1e-15)
+    # unit RMS (up to eps) and scale invariance for rows far above eps
+    rng = np.random.default_rng(20)
+    y = rng.standard_normal((5, 64)) * 30.0
+    h = ref.rmsnorm(y, eps)
+    np.testing.assert_allclose(np.sqrt((h ** 2).mean(1)), 1.0, rtol=1e-8)
+    np.testing.assert_allclose(ref.rmsnorm(7.0 * y, eps), h, rtol=1e-8)
+
+
+def test_rmsnorm_qkv_is_norm_then_products():
+    rng = np.random.default_rng(21)
+    n, d, Hq, Hkv, dh = 6, 10, 4, 2, 3
+    x = rng.standard_normal((n, d))
+    wq, wk, wv = rng.standard_normal((d, Hq * dh)), rng.standard_normal((d, Hkv * dh)), rng.standard_normal((d, Hkv * dh))
+    q, k, v = ref.rmsnorm_qkv(x, wq, wk, wv, Hq, Hkv, dh)
+    h = x / np.sqrt((x ** 2).mean(1, keepdims=True) + 1e-6)
+    np.testing.assert_allclose(q.reshape(n, -1), h @ wq, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(k.reshape(n, -1), h @ wk, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(v.reshape(n, -1), h @ wv, rtol=1e-12, atol=1e-13)
+    assert q.shape == (n, Hq, dh) and k.shape == (n, Hkv, dh)
