@@ -76,7 +76,7 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 // MFMA kernel.
 //
 // Workgroup = 8 waves = 256 query rows of one head; wave w owns rows 32w..32w+31. Keys/values come in
-// tiles of 64, staged through LDS in their natural [key][dim] layout, two stages each.
+// tiles of 64, staged through LDS in their natural [key][dim] layout (16-byte chunks swizzled).
 //
 //   S^T = K Q^T   (A = K fragment from LDS, B = Q fragment held in registers for the whole kernel):
 //         with the 32x32 accumulator layout each lane then holds 16 scores of ONE query per 32-key
@@ -91,8 +91,9 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 // of the next), the other only the softmax VALU work of its current tile, and the SIMD co-executes them.
 //     phase 2t   : group 0  PV(t-1), S(t)      group 1  softmax(t-1)
 //     phase 2t+1 : group 0  softmax(t)         group 1  PV(t-1), S(t)
-// K(t) and V(t-1) are read in phases 2t and 2t+1; K(t+1) and V(t) are fetched into registers at the
-// start of phase 2t and written to the other LDS stages at the end of phase 2t+1.
+// K and V tiles go from global memory straight into LDS (no registers in between), K through two stages and
+// V through three; the V fragments of a tile's first key chunk are read during the softmax phase, so the
+// matrix-core phase that follows the barrier starts with MFMAs, not with an exposed LDS round trip.
 //
 // MFMA 32x32x16 operand layout (lane l, i = l%32, h = l/32): A holds row i, k-slots 8h..8h+7;
 // B holds column i, k-slots 8h..8h+7; D register r holds row 8*(r/4) + 4h + r%4 of column i.
@@ -146,14 +147,38 @@ __device__ __forceinline__ bool fa_map_block(const FaMap& mp, int bid, int n_qti
     return true;
 }
 
+// LDS layout of one K or V stage: 64 rows of DH bf16, unpadded (the direct global->LDS loads write 1 KB of
+// consecutive LDS per wave instruction, so rows cannot be padded). Bank conflicts are avoided by an XOR
+// swizzle of the 16-byte chunk index inside each row, different for K and V because they are read
+// differently: K by 16-byte reads of one chunk from 16 consecutive rows, V by transpose reads that touch
+// 4 consecutive rows x 4 consecutive chunks per 32 lanes.
 template <int DH>
 struct FaSmem {
-    static constexpr int KSTR = DH + 8;   // LDS row stride of K (elements): 16 lanes x 16 B hit distinct banks
-    static constexpr int VSTR = DH + 32;  // LDS row stride of V: the 4-row transpose-read groups do
-    static constexpr int K_ELEMS = kFaBN * KSTR;
-    static constexpr int V_ELEMS = kFaBN * VSTR;
-    static constexpr size_t BYTES = 2 * (K_ELEMS + V_ELEMS) * sizeof(__bf16);  // two stages of each
+    static constexpr int CPR = DH / 8;             // 16-byte chunks per row
+    static constexpr int RP = 256 / (DH * 2);      // rows per 256 bytes of LDS (one pass over all banks)
+    static constexpr int STAGE_ELEMS = kFaBN * DH;
+    static constexpr size_t BYTES = 5 * STAGE_ELEMS * sizeof(__bf16);  // two stages of K, three of V
+    __device__ static constexpr int k_swz(int row) { return (row / RP) % CPR; }
+    __device__ static constexpr int v_swz(int row) { return 4 * ((row / RP) % (CPR / 4)); }
 };
+
+// One direct global->LDS load: lane l's 16 bytes at `gptr` land at LDS address lds_base + 16*l. Issued as
+// inline asm so that the compiler's wait-count bookkeeping does not tie every later LDS read to it; the
+// kernel waits for these loads explicitly (dma_wait) before the barrier that publishes a stage.
+// (M0 holds the LDS base; naming it as a clobber is what keeps the compiler from caching a value in it.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma_load16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+// waits until at most KEEP of this wave's loads (the most recently issued ones) are still in flight
+template <int KEEP>
+__device__ __forceinline__ void dma_wait_keep() { asm volatile("s_waitcnt vmcnt(%0)" : : "i"(KEEP) : "memory"); }
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
 
 template <int DH>
 __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __restrict__ q,
@@ -166,13 +191,9 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     using SM = FaSmem<DH>;
     constexpr int KC = DH / 16;  // contraction chunks of Q K^T
     constexpr int DB = DH / 32;  // 32-wide output blocks of O^T
-    constexpr int KSTR = SM::KSTR, VSTR = SM::VSTR;
-    constexpr int VEC_PER_ROW = DH / 8;
-    constexpr int LOADS = kFaBN * VEC_PER_ROW / 256;
-    constexpr int ROWS_PER_IT = 256 / VEC_PER_ROW;
     extern __shared__ __attribute__((aligned(16))) unsigned char fa_smem_raw[];
-    __bf16* Kst = reinterpret_cast<__bf16*>(fa_smem_raw);  // two K stages, then two V stages
-    __bf16* Vst = Kst + 2 * SM::K_ELEMS;
+    __bf16* Kst = reinterpret_cast<__bf16*>(fa_smem_raw);  // two K stages, then three V stages
+    __bf16* Vst = Kst + 2 * SM::STAGE_ELEMS;
     __shared__ __attribute__((aligned(16))) int pos_blk[kFaBM];  // original positions of this workgroup's rows
 
     int qt, head;
@@ -209,73 +230,88 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     const int n_tiles = (kv_end + kFaBN - 1) / kFaBN;
     const int wave_kend = causal ? min(n, q0 + 32) : n;  // keys at or beyond this rank are masked for the whole wave
 
-    // global -> register -> LDS staging: the 256 threads of group 0 copy the K tiles, those of group 1 the
-    // V tiles, LOADS 16-byte vectors per thread and tile
-    u32x4 stg[LOADS];
-    const int gtid = tid & 255;
-    const int ld_row = gtid / VEC_PER_ROW, ld_c8 = gtid % VEC_PER_ROW;
-    // 32-bit byte offsets (the launcher checks the tensors are below 2 GiB), advanced by one tile per
-    // load and clamped to the last row, which keeps the address arithmetic to two VALU ops per vector
+    // Staging by direct global->LDS loads, no registers in between: the four waves of group 0 fetch the K
+    // tiles, those of group 1 the V tiles. One wave instruction moves 1 KB = ROWS_PER_DMA rows; lane l
+    // lands in physical chunk l % CPR of row l / CPR, so it fetches the logical chunk that the swizzle maps
+    // there. 32-bit byte offsets (the launcher checks the tensors are below 2 GiB), advanced by one tile per
+    // load and clamped to the last row.
+    constexpr int ROWS_PER_DMA = 64 / SM::CPR;                  // 4 (DH 128) or 8 (DH 64)
+    constexpr int DMAS = kFaBN / ROWS_PER_DMA / 4;              // per wave and tile: 4 or 2
+    const int gw = wave & 3;                                    // wave inside its group
     const uint32_t row_bytes = (uint32_t)Hkv * DH * 2u;
-    const uint32_t col_bytes = ((uint32_t)g * DH + ld_c8 * 8) * 2u;
-    const uint32_t last_off = (uint32_t)(n - 1) * row_bytes + col_bytes;
+    const uint32_t last_row_off = (uint32_t)(n - 1) * row_bytes;
     const uint32_t tile_bytes = (uint32_t)kFaBN * row_bytes;
-    uint32_t ld_off[LOADS];
+    uint32_t dma_off[DMAS];   // byte offset of this lane's row in the current tile (clamped)
+    uint32_t dma_col[DMAS];   // byte offset of this lane's logical chunk inside the row
 #pragma unroll
-    for (int it = 0; it < LOADS; ++it)
-        ld_off[it] = min((uint32_t)(ld_row + ROWS_PER_IT * it) * row_bytes + col_bytes, last_off);
-    const char* ld_base = reinterpret_cast<const char*>(grp == 0 ? k : v);
-    auto load_next_tile = [&]() {  // tiles are fetched strictly in order: 0, 1, 2, ...
+    for (int i = 0; i < DMAS; ++i) {
+        const int r = (gw * DMAS + i) * ROWS_PER_DMA + lane / SM::CPR;  // row in the tile
+        const int pchunk = lane % SM::CPR;
+        const int lchunk = pchunk ^ (grp == 0 ? SM::k_swz(r) : SM::v_swz(r));
+        dma_off[i] = min((uint32_t)r * row_bytes, last_row_off);
+        dma_col[i] = ((uint32_t)g * DH + lchunk * 8) * 2u;
+    }
+    const char* dma_base = reinterpret_cast<const char*>(grp == 0 ? k : v);
+    const uint32_t lds_stage0 = lds_addr(grp == 0 ? Kst : Vst) + (uint32_t)(gw * DMAS * 1024);
+    auto dma_next_tile = [&](int stage) {  // tiles are fetched strictly in order: 0, 1, 2, ...
 #pragma unroll
-        for (int it = 0; it < LOADS; ++it) {
-            stg[it] = *reinterpret_cast<const u32x4*>(ld_base + ld_off[it]);
-            ld_off[it] = min(ld_off[it] + tile_bytes, last_off);
+        for (int i = 0; i < DMAS; ++i) {
+            dma_load16(dma_base + dma_off[i] + dma_col[i],
+                       lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
+            dma_off[i] = min(dma_off[i] + tile_bytes, last_row_off);
         }
     };
-    auto store_rows = [&](__bf16* stage, int stride) {
-#pragma unroll
-        for (int it = 0; it < LOADS; ++it)
-            *reinterpret_cast<u32x4*>(&stage[(ld_row + ROWS_PER_IT * it) * stride + ld_c8 * 8]) = stg[it];
-    };
 
-    // O^T += V^T(t) P^T(t): A = V^T fragment by transpose reads, B = packed P
+    // A fragment of O^T += V^T P^T: V^T block (32 dims of block db) x (16 keys of chunk c) by transpose reads
+    auto v_frag = [&](const __bf16* Vs, int c, int db) {
+        const int kbase_row = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
+        const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
+        // rows kbase_row and kbase_row + 8 have the same swizzle (it repeats every 4 * RP <= 8 rows)
+        const int scol = ((col / 8) ^ SM::v_swz(kbase_row)) * 8 + col % 8;
+        const s16x4 lo = lds_read_tr16(&Vs[kbase_row * DH + scol]);
+        const s16x4 hi = lds_read_tr16(&Vs[(kbase_row + 8) * DH + scol]);
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    // The fragments of key chunk 0 are read during the softmax phase, before the barrier that opens the
+    // matrix-core phase, so that phase starts with MFMAs instead of an exposed LDS round trip.
+    bf16x8 Vpre[DB];
+    auto prefetch_v = [&](int t) {
+        const __bf16* Vs = Vst + (t % 3) * SM::STAGE_ELEMS;
+#pragma unroll
+        for (int db = 0; db < DB; ++db) Vpre[db] = v_frag(Vs, 0, db);
+    };
+    // O^T += V^T(t) P^T(t): A = V^T fragment, B = packed P
     auto pv_mfma = [&](int t) {
-        const __bf16* Vs = Vst + (t & 1) * SM::V_ELEMS;
+        const __bf16* Vs = Vst + (t % 3) * SM::STAGE_ELEMS;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const int kbase_row = 16 * c + 4 * (tg / 2) + ti / 4;  // key row this lane addresses
             const u32x4 pw = {Pw[c][0], Pw[c][1], Pw[c][2], Pw[c][3]};
             const bf16x8 Pf = __builtin_bit_cast(bf16x8, pw);
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const int col = 32 * db + 16 * (tg % 2) + 4 * (ti % 4);
-                const s16x4 lo = lds_read_tr16(&Vs[kbase_row * VSTR + col]);
-                const s16x4 hi = lds_read_tr16(&Vs[(kbase_row + 8) * VSTR + col]);
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), Pf,
+            for (int db = 0; db < DB; ++db)
+                Oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c == 0 ? Vpre[db] : v_frag(Vs, c, db), Pf,
                                                                    Oacc[db], 0, 0, 0);
-            }
         }
-        // issue order: operand reads run four MFMAs ahead, so no MFMA waits for a read issued just before it
+        // issue order: operand reads run DB MFMAs ahead, so no MFMA waits for a read issued just before it
         constexpr int NM = 4 * DB;
-        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
-        for (int i = 0; i < NM - 4; ++i) {
+        for (int i = 0; i < NM - DB; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
     };
     // S^T = K(t) Q^T
     auto qk_mfma = [&](int t) {
-        const __bf16* Ks = Kst + (t & 1) * SM::K_ELEMS;
+        const __bf16* Ks = Kst + (t & 1) * SM::STAGE_ELEMS;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) {
-                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[(32 * kb + j) * KSTR + 16 * kc + 8 * h]);
+                const int krow = 32 * kb + j;
+                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[krow * DH + ((2 * kc + h) ^ SM::k_swz(krow)) * 8]);
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
             }
         }
@@ -347,6 +383,7 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         // sums; only if a sum is not a modest finite number (a score far above the reference, or the
         // first tile, where the reference is still -1e30) the reference moves to the true running
         // maximum, what was accumulated is rescaled, and the tile's probabilities are redone.
+        prefetch_v(t);
         float psum = exp_pack(m);
         if (__any(!(psum < kRowSumLimit))) {
             float c0 = fmaxf(S[0][0], S[1][0]), c1 = fmaxf(S[0][1], S[1][1]);
@@ -373,11 +410,13 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         lsum += psum;
     };
 
-    if (grp == 0) {
-        load_next_tile();
-        store_rows(Kst, KSTR);  // K(0)
+    // K(0) by group 0; V(0) and V(1) by group 1, which waits for V(0) only
+    dma_next_tile(0);
+    if (grp == 1 && n_tiles > 1) {
+        dma_next_tile(1);
+        dma_wait_keep<DMAS>();
     } else {
-        load_next_tile();  // V(0), written to LDS at the end of interval 1
+        dma_wait();
     }
     if (tid < kFaBM) pos_blk[tid] = pos[min(qt * kFaBM + tid, n - 1)];
     // The Q fragments have to be in registers before the loop: if their loads were still in flight at
@@ -389,11 +428,16 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
 
     // Both groups run the same loop (matrix-core phase, barrier, VALU phase, barrier); group 1 is skewed
     // by one barrier interval, so in every interval one group is in its MFMA phase and the other in its
-    // softmax phase. Interval 2t: group 0 MFMA(t), group 1 softmax(t-1); interval 2t+1: group 0
-    // softmax(t), group 1 MFMA(t). K(t+1) and V(t) must be in LDS by the end of interval 2t+1; their
-    // stages were last read in interval 2t-1. Every wave passes the same number of barriers:
-    // waves whose rows cannot see a tile skip its work, not its barriers. The extra round t = n_tiles
-    // only drains P V of the final tile.
+    // softmax phase. Number the barriers 0, 1, 2, ...: group 0 passes barrier 2t between its MFMA and
+    // softmax phases of tile t and barrier 2t+1 after the softmax phase; group 1 passes barrier 0 before
+    // its loop, then 2t+1 and 2t+2.
+    //   K(t+1), two stages: fetched by group 0 after barrier 2t-1 (K(t-1) was last read before it),
+    //     complete before barrier 2t+1, first read after it.
+    //   V(t+2), three stages: fetched by group 1 after barrier 2t+1 (V(t-1) was last read before it),
+    //     complete before barrier 2t+4; group 0 reads its first fragments in the softmax phase of tile
+    //     t+2, right after that barrier. The wave that waits always leaves the newest fetch in flight.
+    // Every wave passes the same number of barriers: waves whose rows cannot see a tile skip its work,
+    // not its barriers. The extra round t = n_tiles only drains P V of the final tile.
     // barrier that orders LDS traffic only: the staging loads in flight must not be waited for here
     auto lds_barrier = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -402,13 +446,16 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     };
     if (grp == 1) lds_barrier();
     for (int t = 0; t <= n_tiles; ++t) {
-        if (grp == 0 && t + 1 < n_tiles) load_next_tile();  // K(t+1), start of interval 2t
+        if (grp == 0 && t + 1 < n_tiles) dma_next_tile((t + 1) & 1);  // K(t+1)
         mfma_phase(t);
-        if (grp == 1 && t < n_tiles) store_rows(Vst + (t & 1) * SM::V_ELEMS, VSTR);  // V(t), end of interval 2t+1
         lds_barrier();
-        if (grp == 1 && t + 1 < n_tiles) load_next_tile();  // V(t+1), start of interval 2t+2
+        const bool v_fetch = grp == 1 && t + 2 < n_tiles;
+        if (v_fetch) dma_next_tile((t + 2) % 3);  // V(t+2)
         valu_phase(t);
-        if (grp == 0 && t + 1 < n_tiles) store_rows(Kst + ((t + 1) & 1) * SM::K_ELEMS, KSTR);  // end of interval 2t+1
+        if (v_fetch)
+            dma_wait_keep<DMAS>();  // V(t+1) has landed, V(t+2) stays in flight
+        else
+            dma_wait();  // group 0: K(t+1); group 1 near the end: everything
         lds_barrier();
     }
     if (grp == 0) lds_barrier();
