@@ -216,6 +216,12 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         const __bf16* qp = q + ((size_t)qrow_c * Hq + head) * DH + 8 * h;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) Qf[kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
+        // Q is scaled once by softmax_scale * log2(e) (rounded to bf16 again), so the MFMA result is already the
+        // exponent in the log2 domain
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Qf[kc][e] = (__bf16)((float)Qf[kc][e] * scale_log2);
     }
     f32x16 Oacc[DB];
 #pragma unroll
@@ -224,7 +230,15 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         for (int r = 0; r < 16; ++r) Oacc[db][r] = 0.f;
     f32x16 S[2];
     uint32_t Pw[4][4];  // P^T of the previous tile as packed bf16 pairs: Pw[c] is the B fragment of key chunk c
-    float m = kMaskedScore, lsum = 0.f;
+    // m is the softmax reference (log2 domain); Cneg holds -m in all 16 accumulator slots and is what every
+    // score accumulation starts from, so S arrives as (score - m) and the common tile needs no subtraction.
+    // It changes only when the reference moves; the empty asm keeps it a register block instead of 16
+    // re-materialised moves per tile.
+    float m = 0.f, lsum = 0.f;
+    f32x16 Cneg;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) Cneg[r] = 0.f;
+    asm volatile("" : "+v"(Cneg));
 
     const int kv_end = causal ? min(n, qt * kFaBM + kFaBM) : n;
     const int n_tiles = (kv_end + kFaBN - 1) / kFaBN;
@@ -307,7 +321,7 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) S[kb][r] = 0.f;
+            for (int r = 0; r < 16; ++r) S[kb][r] = Cneg[r];
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) {
                 const int krow = 32 * kb + j;
@@ -335,17 +349,18 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         if (tile_active(t)) qk_mfma(t);
         __builtin_amdgcn_s_setprio(0);
     };
-    // probabilities of the tile in S relative to `ref`, packed to bf16 pairs into Pw; returns this lane's
-    // part of the row sum. fp32 adds on four chains: a bf16 dot2 would halve the instruction count, but it
-    // executes on the matrix pipe and (measured) serialises with the other group's MFMAs.
-    auto exp_pack = [&](float ref) {
+    // probabilities of the tile from S = score - m (minus `shift` when the reference has just moved), packed
+    // to bf16 pairs into Pw; returns this lane's part of the row sum. fp32 adds on four chains: a bf16 dot2
+    // would halve the instruction count, but it executes on the matrix pipe and (measured) serialises
+    // with the other group's MFMAs.
+    auto exp_pack = [&](bool shifted, float shift) {
         float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(S[kb][r], scale_log2, -ref));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(S[kb][r + 1], scale_log2, -ref));
+                const float p0 = __builtin_amdgcn_exp2f(shifted ? S[kb][r] - shift : S[kb][r]);
+                const float p1 = __builtin_amdgcn_exp2f(shifted ? S[kb][r + 1] - shift : S[kb][r + 1]);
                 ps[(r / 2) % 4] += p0;
                 ps[(r / 2 + 2) % 4] += p1;
                 const bf16x2 pk = {(__bf16)p0, (__bf16)p1};
@@ -379,13 +394,13 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         }
         // Probabilities are taken against a reference m that is NOT the running maximum: any reference
         // gives the same O / sum, it only has to keep exp2 in range. The common tile therefore computes
-        // no row maximum at all: it exponentiates against the current reference and looks at the row
-        // sums; only if a sum is not a modest finite number (a score far above the reference, or the
-        // first tile, where the reference is still -1e30) the reference moves to the true running
-        // maximum, what was accumulated is rescaled, and the tile's probabilities are redone.
+        // no row maximum at all: it exponentiates S (already relative to m) and looks at the row sums;
+        // only if a sum is not a modest finite number (a score far above the reference), and always on
+        // the first tile, the reference moves to the true running maximum, what was accumulated is
+        // rescaled, and the tile's probabilities are redone.
         prefetch_v(t);
-        float psum = exp_pack(m);
-        if (__any(!(psum < kRowSumLimit))) {
+        float psum = exp_pack(false, 0.f);
+        if (t == 0 || __any(!(psum < kRowSumLimit))) {
             float c0 = fmaxf(S[0][0], S[1][0]), c1 = fmaxf(S[0][1], S[1][1]);
             float c2 = fmaxf(S[0][2], S[1][2]), c3 = fmaxf(S[0][3], S[1][3]);
 #pragma unroll
@@ -395,17 +410,22 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
                 c2 = fmaxf(fmaxf(c2, S[0][r + 2]), S[1][r + 2]);
                 c3 = fmaxf(fmaxf(c3, S[0][r + 3]), S[1][r + 3]);
             }
-            float mx = fmaxf(fmaxf(c0, c1), fmaxf(c2, c3));
+            float mx = fmaxf(fmaxf(c0, c1), fmaxf(c2, c3));  // tile maximum relative to m
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx * scale_log2);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-            m = m_new;
+            // The first tile (key 0 is visible to every row, so mx is finite) sets the reference outright,
+            // nothing has been accumulated yet; later the reference only rises.
+            const float shift = t == 0 ? mx : fmaxf(mx, 0.f);
+            const float alpha = t == 0 ? 1.f : __builtin_amdgcn_exp2f(-shift);
+            m += shift;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) Cneg[r] = -m;
+            asm volatile("" : "+v"(Cneg));
             lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) Oacc[db][r] *= alpha;
-            psum = exp_pack(m);
+            psum = exp_pack(true, shift);
         }
         lsum += psum;
     };
