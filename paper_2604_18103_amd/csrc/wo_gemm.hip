@@ -118,32 +118,40 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b(const __bf16* p) {
 
 enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1 };
 
-template <int EPI>
+// MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
+// grid: when the 256-row tiles do not fill a whole number of rounds over the compute units, the tiles of
+// the last, partly filled round are cut in two so that twice as many units share them.
+// Workgroup b handles tile first_tile + b (MB = 4) or half b % 2 of tile first_tile + b / 2 (MB = 2).
+template <int EPI, int MB>
 __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restrict__ A,
                                                            const __bf16* __restrict__ B, int M, int K, int N,
                                                            const __bf16* __restrict__ x,
                                                            __bf16* __restrict__ out,  // x_next or C
                                                            float* __restrict__ partials,
-                                                           float* __restrict__ delta_dbg, int n_mtiles) {
+                                                           float* __restrict__ delta_dbg, int n_mtiles,
+                                                           int first_tile) {
+    constexpr int BM = 64 * MB;   // rows of this workgroup's tile
+    constexpr int WM = 32 * MB;   // rows of a wave's tile
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
     __bf16* smem = reinterpret_cast<__bf16*>(gemm_smem_raw);
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int j = lane % 32, h = lane / 32;
     const int wm = wave / 2, wn = wave % 2;
     // consecutive workgroups walk down M inside one column tile, so the B panel stays hot in L2
-    const int tile_m = (int)blockIdx.x % n_mtiles, tile_n = (int)blockIdx.x / n_mtiles;
-    const int m0 = tile_m * kGM, n0 = tile_n * kGN;
+    const int tile = first_tile + (MB == 4 ? (int)blockIdx.x : (int)blockIdx.x / 2);
+    const int tile_m = tile % n_mtiles, tile_n = tile / n_mtiles;
+    const int m0 = tile_m * kGM + (MB == 4 ? 0 : ((int)blockIdx.x % 2) * BM), n0 = tile_n * kGN;
 
-    f32x16 acc[4][4];
+    f32x16 acc[MB][4];
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < MB; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
     // global -> register staging of the next K step: A tile 256x64 and B tile 64x256, 8 x 16 B each per thread
-    constexpr int AL = kGM * kGK / 8 / 256, BL = kGK * kGN / 8 / 256;
+    constexpr int AL = BM * kGK / 8 / 256, BL = kGK * kGN / 8 / 256;
     u32x4 ra[AL], rb[BL];
     const int a_row = tid / 8, a_c8 = tid % 8;    // + 32 rows per step
     const int b_row = tid / 32, b_c8 = tid % 32;  // + 8 rows per step
@@ -185,10 +193,10 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
         const __bf16* sb = sa + kGAElems;
 #pragma unroll
         for (int ks = 0; ks < kGK / 16; ++ks) {
-            bf16x8 Af[4], Bf[4];
+            bf16x8 Af[MB], Bf[4];
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
-                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[(wm * 128 + 32 * a + j) * kGAStr + 16 * ks + 8 * h]);
+            for (int a = 0; a < MB; ++a)
+                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[(wm * WM + 32 * a + j) * kGAStr + 16 * ks + 8 * h]);
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*128 + 32b + 16*(tg%2) + 4*(ti%4)
@@ -199,7 +207,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                 Bf[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
 #pragma unroll
-            for (int a = 0; a < 4; ++a)
+            for (int a = 0; a < MB; ++a)
 #pragma unroll
                 for (int b = 0; b < 4; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[a], Bf[b], acc[a][b], 0, 0, 0);
@@ -217,6 +225,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
         compute_step(kt & 1);
         // the other stage was last read in step kt-1, which every wave left through the barrier below
         store_tiles((kt + 1) & 1);
+        if (MB == 4) {
         __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -235,6 +244,27 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
         }
+        } else {
+            // half tile, 32 MFMAs per step: 10 fragment reads per 16-wide slice, 12 loads, 12 LDS writes
+            __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+#pragma unroll
+            for (int i = 0; i < 6; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+#pragma unroll
+            for (int i = 0; i < 12; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            }
+        }
         lds_barrier();
     }
     compute_step((n_ksteps - 1) & 1);
@@ -252,14 +282,14 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
     auto fetch_x = [&](int a, bf16x8* dst) {
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
-            const int gm = min(m0 + wm * 128 + 32 * a + 4 * step + e_row, M - 1);
+            const int gm = min(m0 + wm * WM + 32 * a + 4 * step + e_row, M - 1);
             dst[step] = *reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + min(gn_e, N - 8));
         }
     };
     if (EPI == EPI_RESIDUAL_NORM) fetch_x(0, xv[0]);
 #pragma unroll
-    for (int a = 0; a < 4; ++a) {
-        if (EPI == EPI_RESIDUAL_NORM && a + 1 < 4) fetch_x(a + 1, xv[(a + 1) & 1]);
+    for (int a = 0; a < MB; ++a) {
+        if (EPI == EPI_RESIDUAL_NORM && a + 1 < MB) fetch_x(a + 1, xv[(a + 1) & 1]);
 #pragma unroll
         for (int b = 0; b < 4; ++b)
 #pragma unroll
@@ -269,7 +299,7 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
 #pragma unroll
         for (int step = 0; step < 8; ++step) {
             const int lr = 4 * step + e_row;
-            const int gm = m0 + wm * 128 + 32 * a + lr;
+            const int gm = m0 + wm * WM + 32 * a + lr;
             const f32x4 d0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8]);
             const f32x4 d1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8 + 4]);
             const float dv[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
@@ -343,16 +373,46 @@ int norm_partials_per_row(int d, int dtype) {
     return 2 * ((d + kGN - 1) / kGN);
 }
 
+// Number of compute units of the current device (queried once; the library serves one GPU).
+static int compute_units() {
+    static const int n = [] {
+        int dev = 0, cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        return cu;
+    }();
+    return n;
+}
+
+// 256x256 tiles for every whole round over the compute units; if the tiles left over would occupy at most
+// half of the units, they are run as 128-row half tiles by a second launch (same kernel, MB = 2).
+template <int EPI>
+static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
+                               __bf16* out, float* partials, float* delta_dbg, hipStream_t s) {
+    static const hipError_t attr4 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         (int)kGemmSmemBytes);
+    static const hipError_t attr2 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 2>,
+                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                         (int)kGemmSmemBytes);
+    if (attr4 != hipSuccess || attr2 != hipSuccess) return DASH_ERR_HIP;
+    const int mt = (M + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN, tiles = mt * nt;
+    const int cu = compute_units();
+    int rest = cu > 0 ? tiles % cu : 0;
+    if (2 * rest > cu) rest = 0;
+    const int full = tiles - rest;
+    if (full > 0)
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(256), kGemmSmemBytes, s, A, B, M, K, N, x,
+                           out, partials, delta_dbg, mt, 0);
+    if (rest > 0)
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(256), kGemmSmemBytes, s, A, B, M, K, N,
+                           x, out, partials, delta_dbg, mt, full);
+    return launch_status();
+}
+
 static dash_status launch_gemm_store(const __bf16* A, const __bf16* B, int M, int K, int N, __bf16* C,
                                      hipStream_t s) {
-    const int mt = (M + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN;
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_STORE>,
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                        (int)kGemmSmemBytes);
-    if (attr != hipSuccess) return DASH_ERR_HIP;
-    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_STORE>), dim3(mt * nt), dim3(256), kGemmSmemBytes, s, A, B, M, K, N,
-                       (const __bf16*)nullptr, C, (float*)nullptr, (float*)nullptr, mt);
-    return launch_status();
+    return launch_gemm<EPI_STORE>(A, B, M, K, N, nullptr, C, nullptr, nullptr, s);
 }
 
 dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o, const void* w_o,
@@ -366,15 +426,8 @@ dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o
                            (const float*)x, n, K, N, (float*)x_next, partials, delta_dbg);
         return launch_status();
     }
-    const int mt = (n + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN;
-    static const hipError_t attr = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_RESIDUAL_NORM>,
-                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                        (int)kGemmSmemBytes);
-    if (attr != hipSuccess) return DASH_ERR_HIP;
-    hipLaunchKernelGGL((gemm_mfma_kernel<EPI_RESIDUAL_NORM>), dim3(mt * nt), dim3(256), kGemmSmemBytes, s,
-                       (const __bf16*)o, (const __bf16*)w_o, n, K, N, (const __bf16*)x, (__bf16*)x_next,
-                       partials, delta_dbg, mt);
-    return launch_status();
+    return launch_gemm<EPI_RESIDUAL_NORM>((const __bf16*)o, (const __bf16*)w_o, n, K, N, (const __bf16*)x,
+                                          (__bf16*)x_next, partials, delta_dbg, s);
 }
 
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
