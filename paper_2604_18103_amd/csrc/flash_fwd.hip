@@ -84,13 +84,12 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 //   O^T += V^T P^T (A = V^T fragment via LDS transpose reads, B = P^T): the accumulator registers of
 //         S^T, converted to bf16, already ARE the B fragment - no shuffle, no LDS round trip.
 //
-// Per score the softmax costs about as many VALU cycles as the two MFMAs cost matrix-core cycles, and a
-// wave that runs them back to back leaves each pipe idle half the time. So the eight waves form two
-// groups (waves 0-3 and 4-7; wave w and w+4 share a SIMD) that alternate roles, separated by workgroup
-// barriers: in every phase one group issues only MFMAs (O += P V of the previous tile, then S = K Q^T
-// of the next), the other only the softmax VALU work of its current tile, and the SIMD co-executes them.
-//     phase 2t   : group 0  PV(t-1), S(t)      group 1  softmax(t-1)
-//     phase 2t+1 : group 0  softmax(t)         group 1  PV(t-1), S(t)
+// A wave that runs MFMAs and softmax back to back leaves each pipe idle half the time. So the eight waves
+// form two groups (waves 0-3 and 4-7; wave w and w+4 share a SIMD) that run the same loop body - an MFMA
+// stretch (O += P V of the previous tile, then S = K Q^T of the next) followed by the softmax of that tile -
+// but pass the one workgroup barrier of a round at different places, so that between two barriers
+//     group 0 runs  MFMA stretch(t), softmax(t)        group 1 runs  softmax(t-1), MFMA stretch(t)
+// and the SIMD co-executes one group's MFMAs with the other group's VALU work.
 // K and V tiles go from global memory straight into LDS (no registers in between), K through two stages and
 // V through three; the V fragments of a tile's first key chunk are read during the softmax phase, so the
 // matrix-core phase that follows the barrier starts with MFMAs, not with an exposed LDS round trip.
@@ -464,21 +463,30 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     };
-    if (grp == 1) lds_barrier();
+    // One barrier per round and wave, at different places of the same loop: group 0 passes it after its softmax
+    // phase, group 1 between its MFMA and softmax phases. Round r (between barriers r-1 and r) is therefore
+    //     group 0: MFMA stretch of tile r (P V of tile r-1, S of tile r), then softmax of tile r
+    //     group 1: softmax of tile r-1, then the MFMA stretch of tile r
+    // so a SIMD sees the two roles in opposite order, and where one stretch outlasts the other the two MFMA
+    // stretches may overlap instead of waiting for each other.
+    //   K(r+1) is requested by group 0 at the start of round r, V(r+1) by group 1 (so V(1) already before
+    //   the loop); both are complete before barrier r. K(r) is read in round r only: two stages. V(r) is read
+    //   in round r (first fragments, group 0's softmax) and in round r+1 (P V of tile r, group 1's first
+    //   fragments): three stages.
     for (int t = 0; t <= n_tiles; ++t) {
         if (grp == 0 && t + 1 < n_tiles) dma_next_tile((t + 1) & 1);  // K(t+1)
         mfma_phase(t);
-        lds_barrier();
-        const bool v_fetch = grp == 1 && t + 2 < n_tiles;
-        if (v_fetch) dma_next_tile((t + 2) % 3);  // V(t+2)
+        if (grp == 1) {
+            dma_wait();  // V(t+1)
+            lds_barrier();
+            if (t + 2 < n_tiles) dma_next_tile((t + 2) % 3);  // V(t+2)
+        }
         valu_phase(t);
-        if (v_fetch)
-            dma_wait_keep<DMAS>();  // V(t+1) has landed, V(t+2) stays in flight
-        else
-            dma_wait();  // group 0: K(t+1); group 1 near the end: everything
-        lds_barrier();
+        if (grp == 0) {
+            dma_wait();  // K(t+1)
+            lds_barrier();
+        }
     }
-    if (grp == 0) lds_barrier();
 
     lsum += __shfl_xor(lsum, 32);
     const float inv = 1.0f / lsum;
