@@ -32,6 +32,16 @@ def test_bf16_narrow_layer(cfg):
     print(cfg.name, rep)
 
 
+@pytest.mark.parametrize("heads", [(6, 3), (32, 16), (8, 8)], ids=lambda h: f"hq{h[0]}_hkv{h[1]}")
+def test_bf16_head_layouts(heads):
+    """Head counts that take the other branches of the attention kernel's work map: 3 KV heads (no
+    XCD-aligned map), 16 KV heads (two KV heads per XCD), and plain multi-head attention (group size 1)."""
+    hq, hkv = heads
+    cfg = I.LayerConfig(f"heads_{hq}_{hkv}", "bf16", 2500, 700, 256, hq, hkv, 64, 0.3, seed=21 + hq)
+    rep, g, o = P.full_parity(cfg)
+    print(cfg.name, rep)
+
+
 def test_bf16_qwen_shape_ragged():
     """Qwen2.5-7B layer shape (hidden 3584, 28/4 heads, head_dim 128) at a length that is not a
     multiple of any tile (query tile 128, key tile 64, GEMM tile 256)."""
