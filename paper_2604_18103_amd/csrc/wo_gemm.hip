@@ -96,18 +96,22 @@ __global__ __launch_bounds__(256) void wo_simple_kernel(const T* __restrict__ A,
 
 // ------------------------------------------------------------------------------------------------
 // MFMA kernel (bf16): C[M,N] = A[M,K] B[K,N], A and B row-major.
-// Workgroup tile 256x256, K step 32; 4 waves in 2x2, each wave 128x128 = 4x4 MFMA 32x32x16 blocks
-// (256 fp32 accumulator registers per lane). A fragments are 16-byte LDS reads from the [m][k] tile;
-// B fragments come from the natural [k][n] tile through LDS transpose reads.
+// Workgroup tile 256x256, K step 64; 8 waves in 2 (M) x 4 (N), two per SIMD, each wave 128x64 = 4x2 MFMA
+// 32x32x16 blocks (128 fp32 accumulator registers per lane). A fragments are 16-byte LDS reads from the
+// [m][k] tile; B fragments come from the natural [k][n] tile through LDS transpose reads.
+// The tiles of a K step go from global memory straight into LDS (no registers in between). Such a load
+// writes 1 KB of consecutive LDS per wave instruction, so rows cannot be padded; bank conflicts are avoided
+// by an XOR swizzle of the 16-byte chunk index inside a row: A (128-byte rows, 16-byte reads of one chunk
+// from 16 consecutive rows) by (row / 2) % 8, B (512-byte rows, transpose reads of 4 rows x 4 chunks per 32
+// lanes) by 4 * (row % 4).
 // ------------------------------------------------------------------------------------------------
 constexpr int kGM = 256, kGN = 256, kGK = 64;
-constexpr int kGAStr = kGK + 8;     // elements; 144-byte rows: 16 lanes x 16 B land in distinct banks
-constexpr int kGBStr = kGN + 32;    // elements; 576-byte rows for the transpose reads
-constexpr int kEpiStr = 128 + 4;    // fp32 words per staged epilogue row
-constexpr int kGAElems = kGM * kGAStr, kGBElems = kGK * kGBStr;
+constexpr int kGThreads = 512;
+constexpr int kGAElems = kGM * kGK, kGBElems = kGK * kGN;
 constexpr int kGStageElems = kGAElems + kGBElems;
-constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (147456 B)
-static_assert(kGemmSmemBytes >= 4 * 32 * kEpiStr * sizeof(float), "epilogue staging must fit");
+constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (131072 B)
+constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row
+static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float), "epilogue staging must fit");
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -116,6 +120,18 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b(const __bf16* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
+// One direct global->LDS load: lane l's 16 bytes at `gptr` land at LDS address lds_base + 16*l. Inline asm,
+// so the compiler's wait-count bookkeeping does not tie every later LDS read to it; the kernel waits for
+// these loads explicitly before the barrier that publishes a stage. (M0 holds the LDS base; naming it as a
+// clobber is what keeps the compiler from caching a value in it.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void gemm_dma_load16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
 enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1 };
 
 // MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
@@ -123,166 +139,152 @@ enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1 };
 // the last, partly filled round are cut in two so that twice as many units share them.
 // Workgroup b handles tile first_tile + b (MB = 4) or half b % 2 of tile first_tile + b / 2 (MB = 2).
 template <int EPI, int MB>
-__global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restrict__ A,
-                                                           const __bf16* __restrict__ B, int M, int K, int N,
-                                                           const __bf16* __restrict__ x,
-                                                           __bf16* __restrict__ out,  // x_next or C
-                                                           float* __restrict__ partials,
-                                                           float* __restrict__ delta_dbg, int n_mtiles,
-                                                           int first_tile) {
+__global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* __restrict__ A,
+                                                                 const __bf16* __restrict__ B, int M, int K,
+                                                                 int N, const __bf16* __restrict__ x,
+                                                                 __bf16* __restrict__ out,  // x_next or C
+                                                                 float* __restrict__ partials,
+                                                                 float* __restrict__ delta_dbg, int n_mtiles,
+                                                                 int first_tile) {
     constexpr int BM = 64 * MB;   // rows of this workgroup's tile
     constexpr int WM = 32 * MB;   // rows of a wave's tile
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
     __bf16* smem = reinterpret_cast<__bf16*>(gemm_smem_raw);
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int j = lane % 32, h = lane / 32;
-    const int wm = wave / 2, wn = wave % 2;
+    const int wm = wave / 4, wn = wave % 4;
     // consecutive workgroups walk down M inside one column tile, so the B panel stays hot in L2
     const int tile = first_tile + (MB == 4 ? (int)blockIdx.x : (int)blockIdx.x / 2);
     const int tile_m = tile % n_mtiles, tile_n = tile / n_mtiles;
     const int m0 = tile_m * kGM + (MB == 4 ? 0 : ((int)blockIdx.x % 2) * BM), n0 = tile_n * kGN;
 
-    f32x16 acc[MB][4];
+    f32x16 acc[MB][2];
 #pragma unroll
     for (int a = 0; a < MB; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // global -> register staging of the next K step: A tile 256x64 and B tile 64x256, 8 x 16 B each per thread
-    constexpr int AL = BM * kGK / 8 / 256, BL = kGK * kGN / 8 / 256;
-    u32x4 ra[AL], rb[BL];
-    const int a_row = tid / 8, a_c8 = tid % 8;    // + 32 rows per step
-    const int b_row = tid / 32, b_c8 = tid % 32;  // + 8 rows per step
-    const int gn = min(n0 + b_c8 * 8, N - 8);  // columns beyond N are computed on clamped data and never stored
-    auto load_tiles = [&](int k0) {
+    // Staging. A tile: BM rows of 128 bytes, one load instruction = 8 rows; B tile: 64 rows of 512 bytes,
+    // one instruction = 2 rows. Lane l lands in physical chunk l % (chunks per row) of its row and therefore
+    // fetches the logical chunk that the swizzle maps there. Rows beyond M and columns beyond N are clamped:
+    // they are computed on valid data and never stored.
+    constexpr int ADMA = BM / 8 / 8, BDMA = kGK / 2 / 8;  // load instructions per wave and K step
+    const char* a_ptr[ADMA];
+    const char* b_ptr[BDMA];
 #pragma unroll
-        for (int it = 0; it < AL; ++it) {
-            const int gm = min(m0 + a_row + 32 * it, M - 1);
-            ra[it] = *reinterpret_cast<const u32x4*>(A + (size_t)gm * K + k0 + a_c8 * 8);
+    for (int i = 0; i < ADMA; ++i) {
+        const int row = (wave * ADMA + i) * 8 + lane / 8;
+        const int lchunk = (lane % 8) ^ ((row / 2) % 8);
+        a_ptr[i] = reinterpret_cast<const char*>(A + (size_t)min(m0 + row, M - 1) * K + lchunk * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < BDMA; ++i) {
+        const int row = (wave * BDMA + i) * 2 + lane / 32;
+        const int lchunk = (lane % 32) ^ (4 * (row % 4));
+        b_ptr[i] = reinterpret_cast<const char*>(B + (size_t)row * N + min(n0 + lchunk * 8, N - 8));
+    }
+    const size_t b_step = (size_t)kGK * N * sizeof(__bf16);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
+    const uint32_t lds_a = lds0 + (uint32_t)(wave * ADMA * 1024);
+    const uint32_t lds_b = lds0 + (uint32_t)(kGAElems * 2 + wave * BDMA * 1024);
+    auto dma_next_step = [&](int stage) {  // K steps are fetched strictly in order
+        const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
+#pragma unroll
+        for (int i = 0; i < ADMA; ++i) {
+            gemm_dma_load16(a_ptr[i], lds_a + so + i * 1024);
+            a_ptr[i] += kGK * sizeof(__bf16);
         }
 #pragma unroll
-        for (int it = 0; it < BL; ++it) {
-            const int gk = k0 + b_row + 8 * it;
-            rb[it] = *reinterpret_cast<const u32x4*>(B + (size_t)gk * N + gn);
+        for (int i = 0; i < BDMA; ++i) {
+            gemm_dma_load16(b_ptr[i], lds_b + so + i * 1024);
+            b_ptr[i] += b_step;
         }
-    };
-    auto store_tiles = [&](int stage) {
-        __bf16* sa = smem + stage * kGStageElems;
-        __bf16* sb = sa + kGAElems;
-#pragma unroll
-        for (int it = 0; it < AL; ++it)
-            *reinterpret_cast<u32x4*>(&sa[(a_row + 32 * it) * kGAStr + a_c8 * 8]) = ra[it];
-#pragma unroll
-        for (int it = 0; it < BL; ++it)
-            *reinterpret_cast<u32x4*>(&sb[(b_row + 8 * it) * kGBStr + b_c8 * 8]) = rb[it];
     };
 
     const int tg = lane / 16, ti = lane % 16;
     const int n_ksteps = K / kGK;
-    // barrier that orders LDS traffic only: the global loads of the next step must stay in flight across it
+    // barrier that orders LDS traffic only
     auto lds_barrier = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     };
-    // 64 MFMAs of one K step on the operand stage `st`
+    // 8 * MB MFMAs of one K step on the operand stage `st`
     auto compute_step = [&](int st) {
         const __bf16* sa = smem + st * kGStageElems;
         const __bf16* sb = sa + kGAElems;
 #pragma unroll
         for (int ks = 0; ks < kGK / 16; ++ks) {
-            bf16x8 Af[MB], Bf[4];
+            bf16x8 Af[MB], Bf[2];
 #pragma unroll
-            for (int a = 0; a < MB; ++a)
-                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[(wm * WM + 32 * a + j) * kGAStr + 16 * ks + 8 * h]);
+            for (int a = 0; a < MB; ++a) {
+                const int row = wm * WM + 32 * a + j;
+                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((2 * ks + h) ^ ((row / 2) % 8)) * 8]);
+            }
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*128 + 32b + 16*(tg%2) + 4*(ti%4)
+            for (int b = 0; b < 2; ++b) {
+                // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*64 + 32b + 16*(tg%2) + 4*(ti%4)
                 const int krow = 16 * ks + 8 * (tg / 2) + ti / 4;
-                const int col = wn * 128 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
-                const s16x4 lo = lds_read_tr16_b(&sb[krow * kGBStr + col]);
-                const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGBStr + col]);
+                const int col = wn * 64 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
+                const int scol = ((col / 8) ^ (4 * (krow % 4))) * 8 + col % 8;  // krow + 4 swizzles alike
+                const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
+                const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
                 Bf[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
             }
 #pragma unroll
             for (int a = 0; a < MB; ++a)
 #pragma unroll
-                for (int b = 0; b < 4; ++b)
+                for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[a], Bf[b], acc[a][b], 0, 0, 0);
         }
-    };
-    load_tiles(0);
-    store_tiles(0);
-    __syncthreads();
-    // Steady state: one straight-line block per K step with its issue order pinned - the fragment reads of
-    // the first 16-wide slice up front, then every MFMA paired with one read for a later slice; the
-    // global loads of the next step ride along the first MFMAs and its LDS writes along the last ones,
-    // by which time the loads have had about 1500 cycles to land.
-    for (int kt = 0; kt + 1 < n_ksteps; ++kt) {
-        load_tiles((kt + 1) * kGK);
-        compute_step(kt & 1);
-        // the other stage was last read in step kt-1, which every wave left through the barrier below
-        store_tiles((kt + 1) & 1);
-        if (MB == 4) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 12, 0);
+        // issue order: the fragment reads of the first 16-wide slice up front, then every MFMA paired with
+        // reads for the next slice, so that no MFMA waits for a read issued just before it
+        constexpr int RD = MB + 4, MF = 2 * MB;  // LDS reads and MFMAs per slice: 8 and 8, or 6 and 4
+        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
+        for (int sl = 0; sl < 3; ++sl) {
 #pragma unroll
-        for (int i = 0; i < 20; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, 12, 0);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-        }
-        } else {
-            // half tile, 32 MFMAs per step: 10 fragment reads per 16-wide slice, 12 loads, 12 LDS writes
-            __builtin_amdgcn_sched_group_barrier(0x100, 10, 0);
-#pragma unroll
-            for (int i = 0; i < 12; ++i) {
+            for (int i = 0; i < RD - MF; ++i) {  // half tiles: two reads behind each of the first two MFMAs
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             }
 #pragma unroll
-            for (int i = 0; i < 6; ++i) {
+            for (int i = 0; i < 2 * MF - RD; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
             }
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-#pragma unroll
-            for (int i = 0; i < 12; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            }
         }
+        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
+    };
+    dma_next_step(0);
+    gemm_dma_wait();
+    __syncthreads();
+    // One round per K step: request the tiles of the next step into the other stage (last read in the
+    // previous round, which every wave left through the barrier), run this step's MFMAs, wait for the
+    // tiles, barrier.
+    for (int kt = 0; kt < n_ksteps; ++kt) {
+        if (kt + 1 < n_ksteps) dma_next_step((kt + 1) & 1);
+        compute_step(kt & 1);
+        gemm_dma_wait();
         lds_barrier();
     }
-    compute_step((n_ksteps - 1) & 1);
-    __syncthreads();
     // all waves are past the last barrier: the operand stages are free and are reused by the epilogue
 
-    // Epilogue, per 32-row block of the wave's 128x128 tile: stage the fp32 accumulators in LDS, then every
-    // lane handles 8 consecutive columns of one row - 16-byte x loads, 16-byte x_next stores, in-row sums
-    // over 16 lanes. The x vectors of the next block are fetched before the current one is processed.
+    // Epilogue, per 32-row block of the wave's tile: stage the fp32 accumulators in LDS, then every lane
+    // handles 8 consecutive columns of one row - 16-byte x loads, 16-byte x_next stores, in-row sums over
+    // 8 lanes. The x vectors of the next block are fetched before the current one is processed.
     float* stage = reinterpret_cast<float*>(gemm_smem_raw) + wave * 32 * kEpiStr;
-    const int e_row = lane / 16, e_c8 = lane % 16;
-    const int gn_e = n0 + wn * 128 + 8 * e_c8;
+    const int e_row = lane / 8, e_c8 = lane % 8;
+    const int gn_e = n0 + wn * 64 + 8 * e_c8;
     const bool col_ok = gn_e < N;
-    bf16x8 xv[2][8];
+    bf16x8 xv[2][4];
     auto fetch_x = [&](int a, bf16x8* dst) {
 #pragma unroll
-        for (int step = 0; step < 8; ++step) {
-            const int gm = min(m0 + wm * WM + 32 * a + 4 * step + e_row, M - 1);
+        for (int step = 0; step < 4; ++step) {
+            const int gm = min(m0 + wm * WM + 32 * a + 8 * step + e_row, M - 1);
             dst[step] = *reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + min(gn_e, N - 8));
         }
     };
@@ -291,14 +293,14 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
     for (int a = 0; a < MB; ++a) {
         if (EPI == EPI_RESIDUAL_NORM && a + 1 < MB) fetch_x(a + 1, xv[(a + 1) & 1]);
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r)  // accumulator register r: local row 8*(r/4) + 4h + r%4, column j
                 stage[(8 * (r / 4) + 4 * h + r % 4) * kEpiStr + 32 * b + j] = acc[a][b][r];
         __syncthreads();  // every wave runs the same epilogue schedule, so the barrier is uniform
 #pragma unroll
-        for (int step = 0; step < 8; ++step) {
-            const int lr = 4 * step + e_row;
+        for (int step = 0; step < 4; ++step) {
+            const int lr = 8 * step + e_row;
             const int gm = m0 + wm * WM + 32 * a + lr;
             const f32x4 d0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8]);
             const f32x4 d1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * e_c8 + 4]);
@@ -323,12 +325,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma_kernel(const __bf16* __restr
                     }
                 }
 #pragma unroll
-                for (int off = 8; off > 0; off >>= 1) {
+                for (int off = 4; off > 0; off >>= 1) {
                     sd += __shfl_xor(sd, off);
                     sx += __shfl_xor(sx, off);
                 }
                 if (e_c8 == 0 && gm < M) {
-                    const int p = tile_n * 2 + wn;
+                    const int p = tile_n * 4 + wn;
                     *reinterpret_cast<float2*>(partials + ((size_t)p * M + gm) * 2) = make_float2(sd, sx);
                 }
             } else if (ok) {
@@ -370,7 +372,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__
 
 int norm_partials_per_row(int d, int dtype) {
     if (dtype == DASH_F32) return (d + kSimpleTile - 1) / kSimpleTile;
-    return 2 * ((d + kGN - 1) / kGN);
+    return 4 * ((d + kGN - 1) / kGN);
 }
 
 // Number of compute units of the current device (queried once; the library serves one GPU).
@@ -402,10 +404,10 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
     if (2 * rest > cu) rest = 0;
     const int full = tiles - rest;
     if (full > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(256), kGemmSmemBytes, s, A, B, M, K, N, x,
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
                            out, partials, delta_dbg, mt, 0);
     if (rest > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(256), kGemmSmemBytes, s, A, B, M, K, N,
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
                            x, out, partials, delta_dbg, mt, full);
     return launch_status();
 }
