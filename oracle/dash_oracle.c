@@ -17,6 +17,9 @@
  *                          (Sec. 3.4: blocks run on the compacted active sequence)
  *   - rmsnorm            : the LN of Eq. 1 as unit-gain RMS normalisation (front end
  *                          of a layer chain; sits before the path proper)
+ *   - rope               : rotary position embedding of the backbone applied to q and k
+ *                          with each token's ORIGINAL position (Sec. 3.4: the compacted
+ *                          sequence keeps the position ids); front end, before the path
  *   - project            : the output projection that completes U (Sec. 3.1:
  *                          U is the attention output before the residual add)
  *   - residual           : H~ = H + U                  (Sec. 3.1, Alg. 1 step 6)
@@ -157,6 +160,33 @@ int dash_oracle_rmsnorm(const double *x, int64_t m, int32_t d, double eps, doubl
         const double inv = 1.0 / sqrt(ss / (double)d + eps);
         for (int32_t c = 0; c < d; ++c) out[(size_t)i * d + c] = x[(size_t)i * d + c] * inv;
     }
+    return 0;
+}
+
+/*
+ * Rotary position embedding of the Qwen2.5 / Llama-3 backbones the paper evaluates (Sec. 4.1), in the
+ * "rotate-half" pairing those models use: for a head vector u of row t, position p_t = pos[t] (the
+ * token's ORIGINAL position: the compacted active sequence of Sec. 3.4 keeps the position ids) and
+ * i < dh/2 with angle a = p_t * theta^(-2i/dh):
+ *     out[i]        = u[i] cos a - u[i + dh/2] sin a
+ *     out[i + dh/2] = u[i] sin a + u[i + dh/2] cos a.
+ * u, out: [m, heads, dh]; dh even.
+ */
+int dash_oracle_rope(const double *u, const int32_t *pos, int64_t m, int32_t heads, int32_t dh, double theta,
+                     double *out) {
+    if (!u || !pos || !out || m < 0 || heads <= 0 || dh <= 0 || dh % 2 != 0 || !(theta > 0.0)) return -1;
+    const int32_t half = dh / 2;
+    for (int64_t t = 0; t < m; ++t)
+        for (int32_t hd = 0; hd < heads; ++hd) {
+            const double *ur = u + ((size_t)t * heads + hd) * dh;
+            double *orow = out + ((size_t)t * heads + hd) * dh;
+            for (int32_t i = 0; i < half; ++i) {
+                const double a = (double)pos[t] * pow(theta, -2.0 * (double)i / (double)dh);
+                const double c = cos(a), sn = sin(a);
+                orow[i] = ur[i] * c - ur[i + half] * sn;
+                orow[i + half] = ur[i] * sn + ur[i + half] * c;
+            }
+        }
     return 0;
 }
 

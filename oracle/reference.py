@@ -46,6 +46,7 @@ def _load():
     lib.dash_oracle_project.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_residual.argtypes = [dp, dp, C.c_int64, C.c_int32, dp]
     lib.dash_oracle_rmsnorm.argtypes = [dp, C.c_int64, C.c_int32, C.c_double, dp]
+    lib.dash_oracle_rope.argtypes = [dp, i32p, C.c_int64, C.c_int32, C.c_int32, C.c_double, dp]
     lib.dash_oracle_scores.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_decide_threshold.argtypes = [dp, C.c_int64, C.c_double, C.c_int64, C.c_int64, u8p]
     lib.dash_oracle_decide_topk.argtypes = [dp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, u8p]
@@ -121,13 +122,28 @@ def rmsnorm(x, eps=1e-6) -> np.ndarray:
     return out
 
 
-def rmsnorm_qkv(x, w_q, w_k, w_v, n_q_heads, n_kv_heads, head_dim, eps=1e-6):
-    """Front end of a layer in a chain: h = rmsnorm(x); q, k, v = h @ W_q, h @ W_k, h @ W_v."""
+def rope(u, pos, theta) -> np.ndarray:
+    """Rotary position embedding (rotate-half pairing) of u [m, heads, dh] with original positions pos [m]."""
+    u = _f64(u)
+    m, heads, dh = u.shape
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    assert pos.shape == (m,)
+    out = np.empty_like(u)
+    _check(_load().dash_oracle_rope(_ptr(u, C.c_double), _ptr(pos, C.c_int32), m, heads, dh, float(theta),
+                                    _ptr(out, C.c_double)), "rope")
+    return out
+
+
+def rmsnorm_qkv(x, w_q, w_k, w_v, n_q_heads, n_kv_heads, head_dim, eps=1e-6, pos=None, rope_theta=None):
+    """Front end of a layer in a chain: h = rmsnorm(x); q, k, v = h @ W_q, h @ W_k, h @ W_v; with
+    rope_theta, q and k are then rotated by their original positions pos."""
     h = rmsnorm(x, eps)
     n = h.shape[0]
     q = project(h, w_q).reshape(n, n_q_heads, head_dim)
     k = project(h, w_k).reshape(n, n_kv_heads, head_dim)
     v = project(h, w_v).reshape(n, n_kv_heads, head_dim)
+    if rope_theta is not None:
+        q, k = rope(q, pos, rope_theta), rope(k, pos, rope_theta)
     return q, k, v
 
 

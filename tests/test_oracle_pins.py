@@ -364,3 +364,66 @@ def test_rmsnorm_qkv_is_norm_then_products():
     np.testing.assert_allclose(k.reshape(n, -1), h @ wk, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(v.reshape(n, -1), h @ wv, rtol=1e-12, atol=1e-13)
     assert q.shape == (n, Hq, dh) and k.shape == (n, Hkv, dh)
+
+
+# ---------------------------------------------------------------- rotary embedding of the front end
+
+def test_rope_is_a_rotation_by_position_times_frequency():
+    """Each (i, i + dh/2) pair, read as a complex number, is multiplied by exp(j * pos * theta^(-2i/dh))."""
+    rng = np.random.default_rng(30)
+    m, heads, dh, theta = 7, 3, 8, 10000.0
+    u = rng.standard_normal((m, heads, dh))
+    pos = np.array([0, 1, 2, 5, 17, 1000, 131071], dtype=np.int32)
+    got = ref.rope(u, pos, theta)
+    z = u[..., : dh // 2] + 1j * u[..., dh // 2:]
+    freq = theta ** (-np.arange(dh // 2) * 2.0 / dh)
+    zr = z * np.exp(1j * pos[:, None, None].astype(np.float64) * freq[None, None, :])
+    np.testing.assert_allclose(got[..., : dh // 2], zr.real, rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(got[..., dh // 2:], zr.imag, rtol=1e-9, atol=1e-9)
+    # position 0 leaves the vector alone; every position preserves the norm of every head vector
+    np.testing.assert_array_equal(got[0], u[0])
+    np.testing.assert_allclose(np.linalg.norm(got, axis=-1), np.linalg.norm(u, axis=-1), rtol=1e-12)
+
+
+def test_rope_hand_values():
+    # dh = 2: a single frequency 1, so position p rotates (a, b) by p radians
+    u = np.array([[[1.0, 0.0]], [[0.0, 2.0]], [[3.0, 4.0]]])
+    pos = np.array([1, 2, 3], dtype=np.int32)
+    got = ref.rope(u, pos, 10000.0)
+    np.testing.assert_allclose(got[0, 0], [math.cos(1.0), math.sin(1.0)], rtol=1e-15)
+    np.testing.assert_allclose(got[1, 0], [-2.0 * math.sin(2.0), 2.0 * math.cos(2.0)], rtol=1e-15)
+    np.testing.assert_allclose(got[2, 0], [3 * math.cos(3.0) - 4 * math.sin(3.0), 3 * math.sin(3.0) + 4 * math.cos(3.0)],
+                               rtol=1e-15)
+    # dh = 4, theta = 100: frequencies 1 and 100^(-1/2) = 0.1; pairs are (0, 2) and (1, 3)
+    u4 = np.array([[[1.0, 1.0, 0.0, 0.0]]])
+    got4 = ref.rope(u4, np.array([10], dtype=np.int32), 100.0)
+    np.testing.assert_allclose(got4[0, 0], [math.cos(10.0), math.cos(1.0), math.sin(10.0), math.sin(1.0)], rtol=1e-12)
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    """The reason it must be fed original positions: q.k after rotation depends on pos_q - pos_k alone, so a
+    compacted sequence scored with compacted ranks would see different attention logits."""
+    rng = np.random.default_rng(31)
+    dh, theta = 16, 1.0e6
+    q = rng.standard_normal((1, 1, dh)); k = rng.standard_normal((1, 1, dh))
+    def dot(pq, pk):
+        return float((ref.rope(q, np.array([pq], dtype=np.int32), theta) *
+                      ref.rope(k, np.array([pk], dtype=np.int32), theta)).sum())
+    np.testing.assert_allclose(dot(100, 40), dot(5060, 5000), rtol=1e-9, atol=1e-9)
+    np.testing.assert_allclose(dot(7, 7), float((q * k).sum()), rtol=1e-12)
+    assert abs(dot(100, 40) - dot(100, 41)) > 1e-6      # and it does depend on the difference
+
+
+def test_rmsnorm_qkv_with_rope_rotates_q_and_k_only():
+    rng = np.random.default_rng(32)
+    n, d, Hq, Hkv, dh = 5, 12, 4, 2, 6
+    x = rng.standard_normal((n, d))
+    wq, wk, wv = rng.standard_normal((d, Hq * dh)), rng.standard_normal((d, Hkv * dh)), rng.standard_normal((d, Hkv * dh))
+    pos = np.array([0, 3, 4, 90, 91], dtype=np.int32)
+    q0, k0, v0 = ref.rmsnorm_qkv(x, wq, wk, wv, Hq, Hkv, dh)
+    q1, k1, v1 = ref.rmsnorm_qkv(x, wq, wk, wv, Hq, Hkv, dh, pos=pos, rope_theta=5.0e5)
+    np.testing.assert_array_equal(v1, v0)
+    np.testing.assert_allclose(q1, ref.rope(q0, pos, 5.0e5), rtol=1e-15)
+    np.testing.assert_allclose(k1, ref.rope(k0, pos, 5.0e5), rtol=1e-15)
+    np.testing.assert_array_equal(q1[0], q0[0])          # position 0
+    assert np.abs(q1[1] - q0[1]).max() > 1e-3
