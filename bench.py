@@ -64,7 +64,8 @@ def cpu_baseline(cfg, L, rows_target=3072):
 
 
 def run_chain_bench(args, cfg, n_layers=8):
-    """Eight attention-only layers (RMSNorm + q/k/v projections + the layer step), halting the lowest 20 %
+    """Eight attention-only layers (RMSNorm + q/k/v projections + rotary embedding at the original positions
+    + the layer step), halting the lowest 20 %
     of the active scores after every layer (on-device TopK), the compacted output of one layer feeding the
     next. A step = the whole chain; per-layer n_active and time are reported."""
     import numpy as np
@@ -78,15 +79,16 @@ def run_chain_bench(args, cfg, n_layers=8):
     x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)
     idx0 = torch.from_numpy(I.make_active_idx(cfg.N, cfg.n, cfg.seed)).cuda()
     state = CH.alloc_chain(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n)
+    rope_theta = 1.0e6   # Qwen2.5
     for _ in range(max(1, args.warmup)):
-        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac)
+        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, rope_theta=rope_theta)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac)
+        CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, rope_theta=rope_theta)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    layers = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, time_layers=True)
+    layers = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, time_layers=True, rope_theta=rope_theta)
     flops = 0.0
     for r in layers:
         n = r["n_in"]
@@ -103,7 +105,8 @@ def run_chain_bench(args, cfg, n_layers=8):
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "N": cfg.N, "layers": n_layers, "halt_frac_per_layer": cfg.halt_frac,
-                   "hidden": cfg.d, "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim},
+                   "hidden": cfg.d, "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
+                   "rope_theta": rope_theta},
         "chain_tflops": flops / (ms * 1e-3) / 1e12,
         "roofline": {"bound": "mfma", "achieved": flops / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},

@@ -158,6 +158,15 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params *params, const void *x, con
                              const void *w_k, const void *w_v, int32_t n, void *q, void *k, void *v,
                              void *h_scratch, void *hip_stream);
 
+/* Rotary position embedding of the backbone (Qwen2.5 / Llama-3, Sec. 4.1) applied in place to q [n,Hq,dh] and
+ * k [n,Hkv,dh] (bf16, device), with each row's ORIGINAL position active_idx[t]: the compacted active sequence
+ * of Sec. 3.4 keeps the position ids, so this is where active_idx matters numerically. "Rotate-half" pairing:
+ * for i < dh/2 and a = active_idx[t] * theta_base^(-2i/dh):
+ *   u[i], u[i+dh/2] <- u[i] cos a - u[i+dh/2] sin a, u[i] sin a + u[i+dh/2] cos a.
+ * theta_base > 1 (1e6 for Qwen2.5, 5e5 for Llama-3). Part of the front end, like dash_rmsnorm_qkv. */
+dash_status dash_rope_qk(const dash_layer_params *params, void *q, void *k, const int32_t *active_idx, int32_t n,
+                         double theta_base, void *hip_stream);
+
 /* Debug aid: counts rows where active_idx is not strictly increasing or lies outside [0, N)
  * (N < 0: no upper bound) into ONE device int32 *violations. */
 dash_status dash_validate_active_idx(const int32_t *active_idx, int32_t n, int32_t N, int32_t *violations,

@@ -72,9 +72,10 @@ def lib() -> C.CDLL:
     L.dash_compact.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.dash_score_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp]
+    L.dash_rope_qk.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_double, _vp]
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
     for name in ("dash_attn_layer", "dash_flash_fwd", "dash_wo_residual_rownorm", "dash_score_decide",
-                 "dash_compact", "dash_score_rows", "dash_rmsnorm_qkv", "dash_validate_active_idx",
+                 "dash_compact", "dash_score_rows", "dash_rmsnorm_qkv", "dash_rope_qk", "dash_validate_active_idx",
                  "dash_profile_read"):
         getattr(L, name).restype = C.c_int
     _lib = L
@@ -221,6 +222,11 @@ def dash_compact(params, halt_mask, chunk_keep_counts, active_idx, x_next, n, x_
 def dash_score_rows(delta, x, n, d, dtype, score_kind, scores) -> None:
     _check(lib().dash_score_rows(_p(delta), _p(x), int(n), int(d), int(dtype), int(score_kind), _p(scores),
                                  _stream()), "dash_score_rows")
+
+
+def dash_rope_qk(params, q, k, active_idx, n, theta_base) -> None:
+    _check(lib().dash_rope_qk(C.byref(params), _p(q), _p(k), _p(active_idx), int(n), float(theta_base), _stream()),
+           "dash_rope_qk")
 
 
 def dash_rmsnorm_qkv(params, x, w_q, w_k, w_v, n, q, k, v, h_scratch) -> None:

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdash.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "flash_fwd.hip", "wo_gemm.hip", "score_decide.hip", "compact.hip"]
+SOURCES = ["api.hip", "flash_fwd.hip", "wo_gemm.hip", "rope.hip", "score_decide.hip", "compact.hip"]
 
 # packed fp32 instructions are kept off on this target
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

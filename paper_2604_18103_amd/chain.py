@@ -2,6 +2,7 @@
 
 Host driver only: every step runs in the HIP kernels behind the C ABI. Per layer l:
     q, k, v = RMSNorm(x_l) W_q, W_k, W_v          dash_rmsnorm_qkv   (LN of Eq. 1 and the projections)
+    q, k    = RoPE(q, k; original positions S_l)  dash_rope_qk       (optional: rope_theta)
     x_next, scores, halt, x_{l+1}, S_{l+1}, n_{l+1} = dash_attn_layer(..., rule = TOPK, k_keep = n_l - floor(f n_l))
 The compacted output of one layer is the input of the next (Alg. 1 step 4); the survivor count is read back
 once per layer (4 bytes) to size the next launch.
@@ -40,10 +41,11 @@ def alloc_chain(d, n_q_heads, n_kv_heads, head_dim, n_capacity, device="cuda") -
 
 
 def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0: int, weights: list,
-              halt_frac: float, on_layer=None, time_layers=False) -> list:
+              halt_frac: float, on_layer=None, time_layers=False, rope_theta=None) -> list:
     """Run len(weights) layers. weights[l] = dict(w_q, w_k, w_v, w_o) of device tensors.
     Returns per-layer dicts {n_in, n_out, ms}. `on_layer(l, x, idx, n, q, k, v, buf)` is called after each
-    layer (after a device synchronisation) with that layer's inputs and outputs, for checks."""
+    layer (after a device synchronisation) with that layer's inputs and outputs, for checks.
+    With rope_theta, q and k get the backbone's rotary embedding at the tokens' original positions."""
     p = state.params
     x, idx, n = x0, active_idx0, int(n0)
     out = []
@@ -54,6 +56,8 @@ def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
         B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, state.q, state.k, state.v, state.h)
+        if rope_theta is not None:
+            B.dash_rope_qk(p, state.q, state.k, idx, n, rope_theta)
         B.dash_attn_layer(p, x, state.q, state.k, state.v, W["w_o"], idx, n, buf)
         if time_layers:
             e1.record()

@@ -219,6 +219,17 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const vo
     return launch_rmsnorm_qkv(*p, x, w_q, w_k, w_v, n, q, k, v, h_scratch, (hipStream_t)hip_stream);
 }
 
+dash_status dash_rope_qk(const dash_layer_params* p, void* q, void* k, const int32_t* active_idx, int32_t n,
+                         double theta_base, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
+    if (n < 0 || !(theta_base > 1.0)) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!q || !k || !active_idx || !aligned16(q) || !aligned16(k)) return DASH_ERR_INVALID_ARG;
+    return launch_rope_qk(*p, q, k, active_idx, n, theta_base, (hipStream_t)hip_stream);
+}
+
 dash_status dash_validate_active_idx(const int32_t* active_idx, int32_t n, int32_t N, int32_t* violations,
                                      void* hip_stream) {
     if (n < 0 || !violations || (n > 0 && !active_idx)) return DASH_ERR_INVALID_ARG;

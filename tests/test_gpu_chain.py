@@ -1,4 +1,4 @@
-"""Front end (RMSNorm + q/k/v projections) and the layer chain with halting after every layer."""
+"""Front end (RMSNorm + q/k/v projections, rotary embedding) and the layer chain with halting after every layer."""
 import numpy as np
 import pytest
 import torch
@@ -39,7 +39,33 @@ def test_rmsnorm_qkv_matches_oracle():
     assert herr.max() <= 8e-3          # one bf16 rounding
 
 
-def test_chain_teacher_forced_against_oracle():
+@pytest.mark.parametrize("shape", [(28, 4, 128), (6, 3, 64), (5, 1, 128), (8, 8, 64)], ids=lambda t: "hq%d_hkv%d_dh%d" % t)
+def test_rope_qk_matches_oracle(shape):
+    """In-place rotary embedding of q and k with original positions up to 131071 (config 5's prompt length):
+    fp64 angles in the kernel, so the only rounding left is that of the bf16 outputs."""
+    hq, hkv, dh = shape
+    n, N = 517, 131072
+    rng = np.random.default_rng(40 + hq)
+    pos = np.sort(rng.choice(N, size=n, replace=False)).astype(np.int32)
+    pos[0], pos[-1] = 0, N - 1
+    q = I.round_to_bf16(rng.standard_normal((n, hq, dh)))
+    k = I.round_to_bf16(rng.standard_normal((n, hkv, dh)) * 3.0)
+    p = B.make_params(hq * dh, hq, hkv, dh)
+    gq, gk = _dev(q), _dev(k)
+    B.dash_rope_qk(p, gq, gk, torch.from_numpy(pos).cuda(), n, 1.0e6)
+    torch.cuda.synchronize()
+    for got, src in ((gq, q), (gk, k)):
+        want = ref.rope(src, pos, 1.0e6)
+        g = got.float().cpu().numpy()
+        half = dh // 2
+        mag = np.abs(src[..., :half]) + np.abs(src[..., half:])        # |a| + |b| bounds each output
+        mag = np.concatenate([mag, mag], axis=-1)
+        assert np.all(np.abs(g - want) <= 2.0 ** -8 * mag + 1e-30), float(np.abs(g - want).max())
+    assert np.array_equal(gq[0].float().cpu().numpy(), q[0])                # position 0: untouched
+
+
+@pytest.mark.parametrize("rope_theta", [None, 1.0e6], ids=["no_rope", "rope"])
+def test_chain_teacher_forced_against_oracle(rope_theta):
     """Four layers; at every layer the oracle is run on the GPU's actual layer input and active set, so
     band flips cannot compound. Also: the active set only shrinks, halted tokens never return, TopK keeps
     exactly k_keep."""
@@ -58,8 +84,10 @@ def test_chain_teacher_forced_against_oracle():
         idx_np = idx[:n].cpu().numpy()
         W = weights_np[l]
         # front end of this layer
-        oq, ok, ov = ref.rmsnorm_qkv(xs, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+        oq, ok, ov = ref.rmsnorm_qkv(xs, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                                     pos=idx_np, rope_theta=rope_theta)
         assert P.row_rel_err(qs.reshape(n, -1), oq.reshape(n, -1)).max() <= 2e-2
+        assert P.row_rel_err(ks.reshape(n, -1), ok.reshape(n, -1)).max() <= 2e-2
         assert P.row_rel_err(vs.reshape(n, -1), ov.reshape(n, -1)).max() <= 2e-2
         # the path proper, on the values the GPU kernels actually consumed
         k_keep = n - int(cfg.halt_frac * n)
@@ -79,7 +107,7 @@ def test_chain_teacher_forced_against_oracle():
         seen["halted"] |= seen["prev"] - cur
         seen["prev"] = cur
 
-    recs = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, on_layer=check)
+    recs = CH.run_chain(state, x0, idx0, cfg.n, weights, cfg.halt_frac, on_layer=check, rope_theta=rope_theta)
     ns = [r["n_in"] for r in recs] + [recs[-1]["n_out"]]
     assert all(a > b for a, b in zip(ns, ns[1:])), ns
     print("chain n_active:", ns, "band rows:", seen["band"])
