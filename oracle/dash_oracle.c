@@ -20,6 +20,10 @@
  *   - rope               : rotary position embedding of the backbone applied to q and k
  *                          with each token's ORIGINAL position (Sec. 3.4: the compacted
  *                          sequence keeps the position ids); front end, before the path
+ *   - ffn_swiglu         : H^(l+1) = H~ + FFN(LN(H~)) (Alg. 1 step 7) with the gated FFN of the
+ *                          Qwen2.5 / Llama-3 backbones: (silu(h W_gate) * (h W_up)) W_down
+ *   - scatter_rows       : halted tokens keep their last updated state (Sec. 3.4): rows written
+ *                          back to a full-length buffer at their original positions
  *   - project            : the output projection that completes U (Sec. 3.1:
  *                          U is the attention output before the residual add)
  *   - residual           : H~ = H + U                  (Sec. 3.1, Alg. 1 step 6)
@@ -187,6 +191,66 @@ int dash_oracle_rope(const double *u, const int32_t *pos, int64_t m, int32_t hea
                 orow[i + half] = ur[i] * sn + ur[i + half] * c;
             }
         }
+    return 0;
+}
+
+/*
+ * Second half of a block (Alg. 1 step 7): out = x + FFN(LN(x)), LN as in dash_oracle_rmsnorm, FFN the
+ * gated feed-forward of the backbones the paper evaluates (Sec. 4.1):
+ *     h = LN(x);  a = silu(h W_gate) * (h W_up);  out = x + a W_down,     silu(z) = z / (1 + exp(-z)).
+ * x, out: [rows, d]; w_gate, w_up: [d, m]; w_down: [m, d].
+ */
+int dash_oracle_ffn_swiglu(const double *x, const double *w_gate, const double *w_up, const double *w_down,
+                           int64_t rows, int32_t d, int32_t m, double eps, double *out) {
+    if (!x || !w_gate || !w_up || !w_down || !out || rows < 0 || d <= 0 || m <= 0 || eps < 0.0) return -1;
+    int rc = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < rows; ++i) {
+        double *h = (double *)malloc(sizeof(double) * (size_t)d);
+        double *a = (double *)malloc(sizeof(double) * (size_t)m);
+        if (!h || !a) {
+            rc = -2;
+            free(h);
+            free(a);
+            continue;
+        }
+        const double *xr = x + (size_t)i * d;
+        double ss = 0.0;
+        for (int32_t c = 0; c < d; ++c) ss += xr[c] * xr[c];
+        const double inv = 1.0 / sqrt(ss / (double)d + eps);
+        for (int32_t c = 0; c < d; ++c) h[c] = xr[c] * inv;
+        for (int32_t f = 0; f < m; ++f) {
+            double g = 0.0, u = 0.0;
+            for (int32_t c = 0; c < d; ++c) {
+                g += h[c] * w_gate[(size_t)c * m + f];
+                u += h[c] * w_up[(size_t)c * m + f];
+            }
+            a[f] = g / (1.0 + exp(-g)) * u;
+        }
+        double *orow = out + (size_t)i * d;
+        for (int32_t c = 0; c < d; ++c) {
+            double acc = 0.0;
+            for (int32_t f = 0; f < m; ++f) acc += a[f] * w_down[(size_t)f * d + c];
+            orow[c] = xr[c] + acc;
+        }
+        free(h);
+        free(a);
+    }
+    return rc;
+}
+
+/*
+ * Halted tokens keep the state they had when they halted (Sec. 3.4): rows[t] is written to
+ * full[idx[t]] for every t with sel == NULL or sel[t] == sel_value. idx holds original positions in [0, N).
+ */
+int dash_oracle_scatter_rows(const double *rows, const int32_t *idx, const uint8_t *sel, int32_t sel_value,
+                             int64_t n, int32_t d, int64_t N, double *full) {
+    if (!rows || !idx || !full || n < 0 || d <= 0 || N < 0) return -1;
+    for (int64_t t = 0; t < n; ++t) {
+        if (sel && sel[t] != (uint8_t)sel_value) continue;
+        if (idx[t] < 0 || idx[t] >= N) return -3;
+        memcpy(full + (size_t)idx[t] * d, rows + (size_t)t * d, sizeof(double) * (size_t)d);
+    }
     return 0;
 }
 

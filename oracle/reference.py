@@ -47,6 +47,8 @@ def _load():
     lib.dash_oracle_residual.argtypes = [dp, dp, C.c_int64, C.c_int32, dp]
     lib.dash_oracle_rmsnorm.argtypes = [dp, C.c_int64, C.c_int32, C.c_double, dp]
     lib.dash_oracle_rope.argtypes = [dp, i32p, C.c_int64, C.c_int32, C.c_int32, C.c_double, dp]
+    lib.dash_oracle_ffn_swiglu.argtypes = [dp, dp, dp, dp, C.c_int64, C.c_int32, C.c_int32, C.c_double, dp]
+    lib.dash_oracle_scatter_rows.argtypes = [dp, i32p, u8p, C.c_int32, C.c_int64, C.c_int32, C.c_int64, dp]
     lib.dash_oracle_scores.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_decide_threshold.argtypes = [dp, C.c_int64, C.c_double, C.c_int64, C.c_int64, u8p]
     lib.dash_oracle_decide_topk.argtypes = [dp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, u8p]
@@ -145,6 +147,34 @@ def rmsnorm_qkv(x, w_q, w_k, w_v, n_q_heads, n_kv_heads, head_dim, eps=1e-6, pos
     if rope_theta is not None:
         q, k = rope(q, pos, rope_theta), rope(k, pos, rope_theta)
     return q, k, v
+
+
+def ffn_swiglu(x, w_gate, w_up, w_down, eps=1e-6) -> np.ndarray:
+    """Alg. 1 step 7: x + (silu(LN(x) W_gate) * (LN(x) W_up)) W_down."""
+    x, w_gate, w_up, w_down = _f64(x), _f64(w_gate), _f64(w_up), _f64(w_down)
+    rows, d = x.shape
+    m = w_gate.shape[1]
+    assert w_gate.shape == (d, m) and w_up.shape == (d, m) and w_down.shape == (m, d)
+    out = np.empty_like(x)
+    _check(_load().dash_oracle_ffn_swiglu(_ptr(x, C.c_double), _ptr(w_gate, C.c_double), _ptr(w_up, C.c_double),
+                                          _ptr(w_down, C.c_double), rows, d, m, float(eps),
+                                          _ptr(out, C.c_double)), "ffn_swiglu")
+    return out
+
+
+def scatter_rows(rows, idx, full, sel=None, sel_value=1) -> np.ndarray:
+    """full[idx[t]] = rows[t] for the selected t (all if sel is None); returns the updated copy of full."""
+    rows = _f64(rows)
+    full = np.array(full, dtype=np.float64, order="C", copy=True)
+    n, d = rows.shape
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    sp = None
+    if sel is not None:
+        sel = np.ascontiguousarray(sel, dtype=np.uint8)
+        sp = _ptr(sel, C.c_uint8)
+    _check(_load().dash_oracle_scatter_rows(_ptr(rows, C.c_double), _ptr(idx, C.c_int32), sp, int(sel_value), n, d,
+                                            full.shape[0], _ptr(full, C.c_double)), "scatter_rows")
+    return full
 
 
 def residual(x, delta) -> np.ndarray:

@@ -427,3 +427,63 @@ def test_rmsnorm_qkv_with_rope_rotates_q_and_k_only():
     np.testing.assert_allclose(k1, ref.rope(k0, pos, 5.0e5), rtol=1e-15)
     np.testing.assert_array_equal(q1[0], q0[0])          # position 0
     assert np.abs(q1[1] - q0[1]).max() > 1e-3
+
+
+# ---------------------------------------------------------------- second half of a block (Alg. 1 step 7)
+
+def test_ffn_swiglu_scalar_closed_form_and_silu_values():
+    # d = m = 1: LN(x) = x / sqrt(x^2 + eps) = sign(x) (eps -> 0), so out = x + silu(s wg) * (s wu) * wd
+    for x0, wg, wu, wd in ((2.0, 1.0, 3.0, 0.5), (-4.0, 2.0, -1.0, 2.0), (1.0, 0.0, 5.0, 7.0)):
+        got = ref.ffn_swiglu(np.array([[x0]]), np.array([[wg]]), np.array([[wu]]), np.array([[wd]]), eps=0.0)
+        s = math.copysign(1.0, x0)
+        g = s * wg
+        want = x0 + g / (1.0 + math.exp(-g)) * (s * wu) * wd
+        assert abs(got[0, 0] - want) <= 1e-15 * max(1.0, abs(want))
+    # silu through the function: h = [1] (x = 1, eps = 0), w_up = 1, w_down = 1  ->  out - x = silu(w_gate)
+    def silu_via(z):
+        return ref.ffn_swiglu(np.array([[1.0]]), np.array([[z]]), np.array([[1.0]]), np.array([[1.0]]), eps=0.0)[0, 0] - 1.0
+    assert silu_via(0.0) == 0.0
+    assert abs(silu_via(1.0) - 1.0 / (1.0 + math.exp(-1.0))) < 1e-15
+    assert abs(silu_via(40.0) - 40.0) < 1e-12 and abs(silu_via(-40.0)) < 1e-12
+    assert abs(silu_via(-1.2784645427610738) - (-0.27846454276107374)) < 1e-12     # the minimum of silu
+
+
+def test_ffn_swiglu_identities():
+    rng = np.random.default_rng(41)
+    rows, d, m = 6, 10, 14
+    x = rng.standard_normal((rows, d)) * 3.0
+    wg, wu, wd = rng.standard_normal((d, m)), rng.standard_normal((d, m)), rng.standard_normal((m, d))
+    base = ref.ffn_swiglu(x, wg, wu, wd)
+    # W_down = 0 or W_up = 0: the block is the identity
+    np.testing.assert_array_equal(ref.ffn_swiglu(x, wg, wu, np.zeros_like(wd)), x)
+    np.testing.assert_allclose(ref.ffn_swiglu(x, wg, np.zeros_like(wu), wd), x, atol=1e-15)
+    # linear in W_up and in W_down
+    np.testing.assert_allclose(ref.ffn_swiglu(x, wg, 2.0 * wu, wd) - x, 2.0 * (base - x), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(ref.ffn_swiglu(x, wg, wu, -3.0 * wd) - x, -3.0 * (base - x), rtol=1e-12, atol=1e-12)
+    # the update does not see the scale of the row (LN), the residual does
+    np.testing.assert_allclose(ref.ffn_swiglu(5.0 * x, wg, wu, wd) - 5.0 * x, base - x, rtol=1e-6, atol=1e-9)
+    # built from the other oracle pieces and numpy: LN, two products, gate, product, add
+    h = ref.rmsnorm(x)
+    g, u = h @ wg, h @ wu
+    np.testing.assert_allclose(base, x + (g / (1.0 + np.exp(-g)) * u) @ wd, rtol=1e-12, atol=1e-12)
+    # rows are independent
+    np.testing.assert_array_equal(ref.ffn_swiglu(x[2:3], wg, wu, wd), base[2:3])
+
+
+def test_scatter_rows_writes_selected_rows_at_original_positions():
+    rows = np.arange(12.0).reshape(4, 3)
+    idx = np.array([1, 4, 5, 9], dtype=np.int32)
+    full = -np.ones((10, 3))
+    out = ref.scatter_rows(rows, idx, full)
+    for t, p in enumerate(idx):
+        np.testing.assert_array_equal(out[p], rows[t])
+    untouched = np.setdiff1d(np.arange(10), idx)
+    assert np.all(out[untouched] == -1.0) and np.all(full == -1.0)       # the input buffer is not modified
+    halt = np.array([0, 1, 1, 0], dtype=np.uint8)
+    out1 = ref.scatter_rows(rows, idx, full, sel=halt, sel_value=1)
+    np.testing.assert_array_equal(out1[4], rows[1]); np.testing.assert_array_equal(out1[5], rows[2])
+    assert np.all(out1[1] == -1.0) and np.all(out1[9] == -1.0)
+    out0 = ref.scatter_rows(rows, idx, out1, sel=halt, sel_value=0)      # the survivors, later
+    assert np.array_equal(out0[[1, 4, 5, 9]], rows)
+    with pytest.raises(Exception):
+        ref.scatter_rows(rows, np.array([1, 4, 5, 10], dtype=np.int32), full)
