@@ -167,6 +167,27 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params *params, const void *x, con
 dash_status dash_rope_qk(const dash_layer_params *params, void *q, void *k, const int32_t *active_idx, int32_t n,
                          double theta_base, void *hip_stream);
 
+/* Second half of a block (Alg. 1 step 7): x_out = x + FFN(LN(x)) on n rows, LN = RMS normalisation (unit gain,
+ * eps 1e-6), FFN the gated feed-forward of the Qwen2.5 / Llama-3 backbones (Sec. 4.1):
+ *   h = LN(x); a = silu(h W_gate) * (h W_up); x_out = x + a W_down.
+ * bf16 only; d % 64 == 0, m % 64 == 0. device: x, x_out [n,d] (x_out may be x); w_down [m,d];
+ * w_gate_up [d, 2m]: W_gate and W_up interleaved in blocks of 32 columns - columns 64c..64c+31 are columns
+ * 32c..32c+31 of W_gate, columns 64c+32..64c+63 the same columns of W_up (so that one GEMM tile holds gate and
+ * up of the same features and the gating happens in its epilogue).
+ * workspace: device, 256-byte aligned, >= dash_ffn_workspace_bytes(params, n, m) (the normalised rows, the
+ * gated activations [n,m], row-norm partials). */
+size_t dash_ffn_workspace_bytes(const dash_layer_params *params, int32_t n_capacity, int32_t m);
+dash_status dash_ffn_swiglu(const dash_layer_params *params, const void *x, const void *w_gate_up,
+                            const void *w_down, int32_t n, int32_t m, void *x_out, void *workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
+/* Halted tokens keep the state they had when they halted (Sec. 3.4): full[idx[t], :] = rows[t, :] for every t with
+ * select == NULL or select[t] == select_value (e.g. select = halt_mask, select_value = 1: the rows that halt now).
+ * device: rows [n,d], idx [n] original positions, select [n] uint8 or NULL, full [N,d]; dtype as dash_dtype; row
+ * bytes must be a multiple of 16. Rows whose position lies outside [0, N) are skipped. */
+dash_status dash_scatter_rows(const void *rows, const int32_t *idx, const uint8_t *select, int32_t select_value,
+                              int32_t n, int32_t d, int32_t dtype, int32_t N, void *full, void *hip_stream);
+
 /* Debug aid: counts rows where active_idx is not strictly increasing or lies outside [0, N)
  * (N < 0: no upper bound) into ONE device int32 *violations. */
 dash_status dash_validate_active_idx(const int32_t *active_idx, int32_t n, int32_t N, int32_t *violations,

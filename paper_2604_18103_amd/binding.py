@@ -74,9 +74,13 @@ def lib() -> C.CDLL:
     L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp]
     L.dash_rope_qk.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_double, _vp]
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
+    L.dash_ffn_workspace_bytes.restype = C.c_size_t
+    L.dash_ffn_workspace_bytes.argtypes = [pp, C.c_int32, C.c_int32]
+    L.dash_ffn_swiglu.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]
+    L.dash_scatter_rows.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     for name in ("dash_attn_layer", "dash_flash_fwd", "dash_wo_residual_rownorm", "dash_score_decide",
                  "dash_compact", "dash_score_rows", "dash_rmsnorm_qkv", "dash_rope_qk", "dash_validate_active_idx",
-                 "dash_profile_read"):
+                 "dash_profile_read", "dash_ffn_swiglu", "dash_scatter_rows"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -222,6 +226,28 @@ def dash_compact(params, halt_mask, chunk_keep_counts, active_idx, x_next, n, x_
 def dash_score_rows(delta, x, n, d, dtype, score_kind, scores) -> None:
     _check(lib().dash_score_rows(_p(delta), _p(x), int(n), int(d), int(dtype), int(score_kind), _p(scores),
                                  _stream()), "dash_score_rows")
+
+
+def ffn_workspace_bytes(params: LayerParams, n_capacity: int, m: int) -> int:
+    return int(lib().dash_ffn_workspace_bytes(C.byref(params), int(n_capacity), int(m)))
+
+
+def dash_ffn_swiglu(params, x, w_gate_up, w_down, n, m, x_out, workspace) -> None:
+    _check(lib().dash_ffn_swiglu(C.byref(params), _p(x), _p(w_gate_up), _p(w_down), int(n), int(m), _p(x_out),
+                                 _p(workspace), workspace.numel(), _stream()), "dash_ffn_swiglu")
+
+
+def dash_scatter_rows(rows, idx, select, select_value, n, d, dtype, N, full) -> None:
+    _check(lib().dash_scatter_rows(_p(rows), _p(idx), _p(select), int(select_value), int(n), int(d), int(dtype),
+                                   int(N), _p(full), _stream()), "dash_scatter_rows")
+
+
+def interleave_gate_up(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+    """Weight layout dash_ffn_swiglu expects: [d, 2m] with blocks of 32 gate columns followed by the 32 up
+    columns of the same features. Layout preparation done once when weights are loaded."""
+    d, m = w_gate.shape
+    assert w_up.shape == (d, m) and m % 32 == 0
+    return torch.stack((w_gate.reshape(d, m // 32, 32), w_up.reshape(d, m // 32, 32)), dim=2).reshape(d, 2 * m).contiguous()
 
 
 def dash_rope_qk(params, q, k, active_idx, n, theta_base) -> None:

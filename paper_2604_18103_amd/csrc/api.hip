@@ -219,6 +219,37 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const vo
     return launch_rmsnorm_qkv(*p, x, w_q, w_k, w_v, n, q, k, v, h_scratch, (hipStream_t)hip_stream);
 }
 
+size_t dash_ffn_workspace_bytes(const dash_layer_params* p, int32_t n_capacity, int32_t m) {
+    if (check_params(p) != DASH_OK || n_capacity < 0 || m <= 0) return 0;
+    return ffn_workspace_bytes(*p, n_capacity, m);
+}
+
+dash_status dash_ffn_swiglu(const dash_layer_params* p, const void* x, const void* w_gate_up, const void* w_down,
+                            int32_t n, int32_t m, void* x_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
+    if (p->d % 64 != 0 || m <= 0 || m % 64 != 0) return DASH_ERR_UNSUPPORTED;  // K steps of the two GEMMs
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!x || !w_gate_up || !w_down || !x_out || !workspace) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_gate_up) || !aligned16(w_down) || !aligned16(x_out) ||
+        (reinterpret_cast<uintptr_t>(workspace) & 255) != 0)
+        return DASH_ERR_INVALID_ARG;
+    if (workspace_bytes < ffn_workspace_bytes(*p, n, m)) return DASH_ERR_WORKSPACE;
+    return launch_ffn_swiglu(*p, x, w_gate_up, w_down, n, m, x_out, workspace, (hipStream_t)hip_stream);
+}
+
+dash_status dash_scatter_rows(const void* rows, const int32_t* idx, const uint8_t* select, int32_t select_value,
+                              int32_t n, int32_t d, int32_t dtype, int32_t N, void* full, void* hip_stream) {
+    if (n < 0 || d <= 0 || N < 0 || (dtype != DASH_BF16 && dtype != DASH_F32)) return DASH_ERR_INVALID_ARG;
+    if ((size_t)d * (dtype == DASH_BF16 ? 2 : 4) % 16 != 0) return DASH_ERR_UNSUPPORTED;
+    if (n == 0) return DASH_OK;
+    if (!rows || !idx || !full || !aligned16(rows) || !aligned16(full)) return DASH_ERR_INVALID_ARG;
+    return launch_scatter_rows(rows, idx, select, select_value, n, d, dtype, N, full, (hipStream_t)hip_stream);
+}
+
 dash_status dash_rope_qk(const dash_layer_params* p, void* q, void* k, const int32_t* active_idx, int32_t n,
                          double theta_base, void* hip_stream) {
     dash_status st = check_params(p);

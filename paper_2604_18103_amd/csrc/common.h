@@ -67,6 +67,11 @@ dash_status launch_chunk_counts(const uint8_t* halt, int n, int32_t* chunk_count
 dash_status launch_compact(const uint8_t* halt, const int32_t* chunk_counts, const int32_t* active_idx,
                            const void* x_next, int n, int row_bytes, void* x_compact,
                            int32_t* new_active_idx, int32_t* n_active_out, hipStream_t s);
+size_t ffn_workspace_bytes(const dash_layer_params& p, int n, int m);
+dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const void* w_gate_up, const void* w_down,
+                              int n, int m, void* x_out, void* ws, hipStream_t s);
+dash_status launch_scatter_rows(const void* rows, const int32_t* idx, const uint8_t* sel, int sel_value, int n,
+                                int d, int dtype, int N, void* full, hipStream_t s);
 dash_status launch_rope_qk(const dash_layer_params& p, void* q, void* k, const int32_t* active_idx, int n,
                            double theta, hipStream_t s);
 dash_status launch_validate_idx(const int32_t* idx, int n, int N, int32_t* violations, hipStream_t s);

@@ -135,4 +135,36 @@ dash_status launch_validate_idx(const int32_t* idx, int n, int N, int32_t* viola
     return launch_status();
 }
 
+// Halted tokens keep the state they had when they halted (Sec. 3.4): selected rows are written to a
+// full-length buffer at their original positions. One wave per row, 16-byte vectors; rows whose position
+// lies outside [0, N) are skipped.
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const T* __restrict__ rows, const int32_t* __restrict__ idx,
+                                                           const uint8_t* __restrict__ sel, int sel_value, int n,
+                                                           int d, int N, T* __restrict__ full) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int row = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) / kWave);
+    const int lane = threadIdx.x % kWave;
+    if (row >= n) return;
+    if (sel && sel[row] != (uint8_t)sel_value) return;
+    const int p = idx[row];
+    if (p < 0 || p >= N) return;
+    const u32x4* src = reinterpret_cast<const u32x4*>(rows + (size_t)row * d);
+    u32x4* dst = reinterpret_cast<u32x4*>(full + (size_t)p * d);
+    for (int c = lane; c < d / VEC; c += kWave) dst[c] = src[c];
+}
+
+dash_status launch_scatter_rows(const void* rows, const int32_t* idx, const uint8_t* sel, int sel_value, int n,
+                                int d, int dtype, int N, void* full, hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
+    if (dtype == DASH_BF16)
+        hipLaunchKernelGGL(scatter_rows_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, (const __bf16*)rows, idx, sel,
+                           sel_value, n, d, N, (__bf16*)full);
+    else
+        hipLaunchKernelGGL(scatter_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)rows, idx, sel,
+                           sel_value, n, d, N, (float*)full);
+    return launch_status();
+}
+
 }  // namespace dash

@@ -132,7 +132,11 @@ __device__ __forceinline__ void gemm_dma_load16(const void* gptr, uint32_t lds_b
 #pragma clang diagnostic pop
 __device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
-enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1 };
+// EPI_SWIGLU: B holds gate and up columns interleaved in blocks of 32 (columns 64c..64c+31 = gate features
+// 32c..32c+31, columns 64c+32..64c+63 = the up columns of the same features), so a wave's two 32-column
+// accumulator blocks are gate and up of the same 32 features and the epilogue writes silu(gate) * up,
+// N / 2 columns per row.
+enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1, EPI_SWIGLU = 2 };
 
 // MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
 // grid: when the 256-row tiles do not fill a whole number of rounds over the compute units, the tiles of
@@ -298,6 +302,30 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
             for (int r = 0; r < 16; ++r)  // accumulator register r: local row 8*(r/4) + 4h + r%4, column j
                 stage[(8 * (r / 4) + 4 * h + r % 4) * kEpiStr + 32 * b + j] = acc[a][b][r];
         __syncthreads();  // every wave runs the same epilogue schedule, so the barrier is uniform
+        if (EPI == EPI_SWIGLU) {
+            // 4 lanes per row: lane c takes gate columns 8c..8c+7 and the up columns 32 + 8c..
+            const int s_row = lane / 4, s_c = lane % 4;
+            const int gcol = n0 / 2 + wn * 32 + 8 * s_c;  // output column
+#pragma unroll
+            for (int step = 0; step < 2; ++step) {
+                const int lr = 16 * step + s_row;
+                const int gm = m0 + wm * WM + 32 * a + lr;
+                const f32x4 g0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * s_c]);
+                const f32x4 g1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 8 * s_c + 4]);
+                const f32x4 u0 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 32 + 8 * s_c]);
+                const f32x4 u1 = *reinterpret_cast<const f32x4*>(&stage[lr * kEpiStr + 32 + 8 * s_c + 4]);
+                const float gv[8] = {g0[0], g0[1], g0[2], g0[3], g1[0], g1[1], g1[2], g1[3]};
+                const float uv[8] = {u0[0], u0[1], u0[2], u0[3], u1[0], u1[1], u1[2], u1[3]};
+                if (gm < M && gcol < N / 2) {
+                    bf16x8 ov;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ov[e] = (__bf16)(gv[e] / (1.0f + __expf(-gv[e])) * uv[e]);
+                    *reinterpret_cast<bf16x8*>(out + (size_t)gm * (N / 2) + gcol) = ov;
+                }
+            }
+            __syncthreads();
+            continue;
+        }
 #pragma unroll
         for (int step = 0; step < 4; ++step) {
             const int lr = 8 * step + e_row;
@@ -430,6 +458,31 @@ dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o
     }
     return launch_gemm<EPI_RESIDUAL_NORM>((const __bf16*)o, (const __bf16*)w_o, n, K, N, (const __bf16*)x,
                                           (__bf16*)x_next, partials, delta_dbg, s);
+}
+
+size_t ffn_workspace_bytes(const dash_layer_params& p, int n, int m) {
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    return up((size_t)n * p.d * 2) + up((size_t)n * m * 2) +
+           up((size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float));
+}
+
+// out = x + (silu(h W_gate) * (h W_up)) W_down with h = RMSNorm(x) (Alg. 1 step 7): row norm, one GEMM over
+// the interleaved gate/up weight with the gating in its epilogue, one GEMM with the residual epilogue.
+dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const void* w_gate_up, const void* w_down,
+                              int n, int m, void* x_out, void* ws, hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    char* base = reinterpret_cast<char*>(ws);
+    __bf16* h = reinterpret_cast<__bf16*>(base);
+    __bf16* act = reinterpret_cast<__bf16*>(base + up((size_t)n * p.d * 2));
+    float* partials = reinterpret_cast<float*>(base + up((size_t)n * p.d * 2) + up((size_t)n * m * 2));
+    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(blocks), dim3(256), 0, s, (const __bf16*)x, n, p.d, h);
+    dash_status st = launch_gemm<EPI_SWIGLU>(h, (const __bf16*)w_gate_up, n, p.d, 2 * m, nullptr, act, nullptr,
+                                             nullptr, s);
+    if (st != DASH_OK) return st;
+    return launch_gemm<EPI_RESIDUAL_NORM>(act, (const __bf16*)w_down, n, m, p.d, (const __bf16*)x,
+                                          (__bf16*)x_out, partials, nullptr, s);
 }
 
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,

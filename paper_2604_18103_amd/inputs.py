@@ -135,6 +135,17 @@ def make_projection_weights(cfg: LayerConfig, layer: int) -> dict:
     return out
 
 
+def make_ffn_weights(cfg: LayerConfig, layer: int, m: int) -> dict:
+    """Per-layer gated feed-forward weights: W_gate, W_up [d, m] ~ N(0, 1/d), W_down [m, d] ~ N(0, 1/m)."""
+    out = {}
+    for s, (name, shp, fan) in enumerate((("w_gate", (cfg.d, m), cfg.d), ("w_up", (cfg.d, m), cfg.d),
+                                          ("w_down", (m, cfg.d), m))):
+        w = _rng(cfg.seed, 500 + 10 * layer + s).standard_normal(shp, dtype=np.float32)
+        w *= np.float32(1.0 / np.sqrt(fan))
+        out[name] = _store(w, cfg.dtype)
+    return out
+
+
 def sample_rows(n: int, count: int, seed: int, tile: int = 128) -> np.ndarray:
     """Query rows for a row-sampled check: both ends, rows around the first tile
     boundaries, the last ragged tile, the rest seeded-uniform. Sorted, unique."""

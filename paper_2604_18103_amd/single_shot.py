@@ -1,0 +1,100 @@
+"""Driver of the single-shot schedule (Alg. 1): L full blocks, one halting decision at the start layer l_s.
+
+Every step of a block runs in the HIP library:
+    q, k, v      = RMSNorm(H) W_q, W_k, W_v ; RoPE at the original positions        dash_rmsnorm_qkv, dash_rope_qk
+    U, H~        = Attn(.) W_o, H + U                                                dash_flash_fwd + dash_wo_residual_rownorm,
+                                                                                     or dash_attn_layer at l = l_s
+    H_next       = H~ + FFN(LN(H~))                                                  dash_ffn_swiglu
+At l = l_s the layer call also scores the rows (Eq. 2) and picks S* = TopK (Eq. 3). The block still finishes
+on all rows (Alg. 1 step 7 comes before the selection takes effect); then the rows that halt are written to the
+full-length result at their original positions (they keep their last updated state, Sec. 3.4) and the kept rows
+are gathered for the blocks l > l_s. The survivors are written to the result after the last block. One 4-byte
+read-back, at l_s, sizes the later launches.
+"""
+from __future__ import annotations
+
+import dataclasses
+
+import torch
+
+from . import binding as B
+
+
+@dataclasses.dataclass
+class BlockState:
+    params: B.LayerParams
+    m: int
+    buf: B.LayerBuffers
+    q: torch.Tensor
+    k: torch.Tensor
+    v: torch.Tensor
+    h: torch.Tensor
+    o: torch.Tensor
+    partials: torch.Tensor
+    chunk_counts: torch.Tensor
+    x_a: torch.Tensor
+    x_b: torch.Tensor
+    ffn_ws: torch.Tensor
+
+
+def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda") -> BlockState:
+    p = B.make_params(d, n_q_heads, n_kv_heads, head_dim, dtype=B.DASH_BF16, causal=True, rule=B.RULE_NONE)
+    bf = torch.bfloat16
+    cap = int(n_capacity)
+    return BlockState(
+        params=p, m=int(m), buf=B.alloc_layer_buffers(p, cap, device=device),
+        q=torch.empty((cap, n_q_heads, head_dim), dtype=bf, device=device),
+        k=torch.empty((cap, n_kv_heads, head_dim), dtype=bf, device=device),
+        v=torch.empty((cap, n_kv_heads, head_dim), dtype=bf, device=device),
+        h=torch.empty((cap, d), dtype=bf, device=device),
+        o=torch.empty((cap, n_q_heads * head_dim), dtype=bf, device=device),
+        partials=torch.empty((B.norm_partials_per_row(p), cap, 2), dtype=torch.float32, device=device),
+        chunk_counts=torch.empty(((cap + 63) // 64,), dtype=torch.int32, device=device),
+        x_a=torch.empty((cap, d), dtype=bf, device=device),
+        x_b=torch.empty((cap, d), dtype=bf, device=device),
+        ffn_ws=torch.empty((max(B.ffn_workspace_bytes(p, cap, m), 256),), dtype=torch.uint8, device=device))
+
+
+def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | None, k_keep: int,
+                    rope_theta=None, final: torch.Tensor | None = None, on_block=None) -> dict:
+    """Run len(weights) blocks on x0 [N, d] (all N tokens active at the start). weights[l] = dict(w_q, w_k, w_v,
+    w_o, w_gate_up, w_down) of device tensors. l_s = None runs the full model (no halting). k_keep = tokens kept
+    after block l_s. `final` [N, d] receives every token's last state. `on_block(l, x_in, idx, n, st, x_out)` is
+    called after every block (after a device synchronisation) for checks. Returns {n_after, final}."""
+    p, buf = st.params, st.buf
+    N, d = x0.shape
+    if final is None:
+        final = torch.empty_like(x0)
+    idx = torch.arange(N, dtype=torch.int32, device=x0.device)
+    x, n = x0, N
+    spare = [st.x_a, st.x_b]
+    for l, W in enumerate(weights):
+        x_out = spare[l & 1]
+        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, st.q, st.k, st.v, st.h)
+        if rope_theta is not None:
+            B.dash_rope_qk(p, st.q, st.k, idx, n, rope_theta)
+        if l_s is not None and l == l_s:
+            p.rule, p.k_keep = B.RULE_TOPK, int(k_keep)
+            B.dash_attn_layer(p, x, st.q, st.k, st.v, W["w_o"], idx, n, buf)     # H~ in buf.x_next, mask, S*
+            p.rule = B.RULE_NONE
+            B.dash_ffn_swiglu(p, buf.x_next, W["w_gate_up"], W["w_down"], n, st.m, buf.x_next, st.ffn_ws)
+            # the rows that halt now keep this state; the kept rows go on (gathered from the finished block)
+            B.dash_scatter_rows(buf.x_next, idx, buf.halt_mask, 1, n, d, p.dtype, N, final)
+            old_idx = idx
+            idx = torch.empty_like(buf.new_active_idx)
+            B.dash_compact(p, buf.halt_mask, None, old_idx, buf.x_next, n, x_out, idx, buf.n_active_out,
+                           buf.workspace)
+            n_new = int(buf.n_active_out.item())          # the one host read of the schedule
+            if on_block is not None:
+                on_block(l, x, old_idx, n, st, buf.x_next)
+            x, n = x_out, n_new
+        else:
+            B.dash_flash_fwd(p, st.q, st.k, st.v, idx, n, st.o)
+            B.dash_wo_residual_rownorm(p, st.o, W["w_o"], x, n, x_out, st.partials, None, buf.workspace)
+            B.dash_ffn_swiglu(p, x_out, W["w_gate_up"], W["w_down"], n, st.m, x_out, st.ffn_ws)
+            if on_block is not None:
+                torch.cuda.synchronize()
+                on_block(l, x, idx, n, st, x_out)
+            x = x_out
+    B.dash_scatter_rows(x, idx, None, 0, n, d, p.dtype, N, final)
+    return {"n_after": n, "final": final, "idx": idx}

@@ -1,0 +1,150 @@
+"""Second half of a block (gated feed-forward), scatter of halted rows, and the single-shot schedule of Alg. 1."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import reference as ref
+from paper_2604_18103_amd import binding as B
+from paper_2604_18103_amd import inputs as I
+from paper_2604_18103_amd import single_shot as SS
+
+import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _dev(a):
+    return B.to_device(a, B.DASH_BF16)
+
+
+def _f(t):
+    return t.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("shape", [(300, 256, 512), (517, 512, 1408), (64, 128, 64)], ids=lambda t: "n%d_d%d_m%d" % t)
+def test_ffn_swiglu_matches_oracle(shape):
+    n, d, m = shape
+    cfg = I.LayerConfig("ffn", "bf16", n, n, d, 4, 2, 64, 0.3, seed=50 + n)
+    x = I.make_hidden(cfg)
+    W = I.make_ffn_weights(cfg, 0, m)
+    p = P.params_for(cfg)
+    wgu = B.interleave_gate_up(_dev(W["w_gate"]), _dev(W["w_up"]))
+    out = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((B.ffn_workspace_bytes(p, n, m),), dtype=torch.uint8, device="cuda")
+    gx = _dev(x)
+    B.dash_ffn_swiglu(p, gx, wgu, _dev(W["w_down"]), n, m, out, ws)
+    torch.cuda.synchronize()
+    want = ref.ffn_swiglu(x, W["w_gate"], W["w_up"], W["w_down"])
+    err = P.row_rel_err(_f(out), want)
+    assert err.max() <= P.X_TOL["bf16"], err.max()
+    # the update itself, not only the residual it rides on
+    upd_err = np.abs((_f(out) - x) - (want - x)).max(axis=1) / np.maximum(np.abs(want).max(axis=1), 1e-30)
+    assert upd_err.max() <= P.X_TOL["bf16"]
+    assert np.abs(want - x).max() > 1e-2            # the FFN contributes at this scale
+    # in place
+    B.dash_ffn_swiglu(p, gx, wgu, _dev(W["w_down"]), n, m, gx, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(gx, out)
+
+
+def test_scatter_rows_matches_oracle():
+    n, d, N = 333, 256, 1000
+    rng = np.random.default_rng(60)
+    rows = I.round_to_bf16(rng.standard_normal((n, d)))
+    idx = np.sort(rng.choice(N, size=n, replace=False)).astype(np.int32)
+    sel = (rng.random(n) < 0.4).astype(np.uint8)
+    full0 = I.round_to_bf16(rng.standard_normal((N, d)))
+    g_full = _dev(full0)
+    B.dash_scatter_rows(_dev(rows), torch.from_numpy(idx).cuda(), torch.from_numpy(sel).cuda(), 1, n, d, B.DASH_BF16,
+                        N, g_full)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_f(g_full), ref.scatter_rows(rows, idx, full0, sel=sel, sel_value=1))
+    B.dash_scatter_rows(_dev(rows), torch.from_numpy(idx).cuda(), None, 0, n, d, B.DASH_BF16, N, g_full)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_f(g_full), ref.scatter_rows(rows, idx, full0))
+    # positions outside the buffer are skipped, nothing else is touched
+    bad = idx.copy(); bad[5] = N + 3; bad[6] = -1
+    g2 = _dev(full0)
+    B.dash_scatter_rows(_dev(rows), torch.from_numpy(bad).cuda(), None, 0, n, d, B.DASH_BF16, N, g2)
+    torch.cuda.synchronize()
+    keep = np.ones(n, dtype=np.uint8); keep[5] = keep[6] = 0
+    np.testing.assert_array_equal(_f(g2), ref.scatter_rows(rows, np.where(keep == 1, bad, 0).astype(np.int32), full0,
+                                                           sel=keep, sel_value=1))
+
+
+def test_single_shot_schedule_teacher_forced_against_oracle():
+    """Alg. 1 on four blocks with the decision at l_s = 1 (App. A's protected prefix/suffix and rounding):
+    every block is checked against the oracle run on the block's actual GPU input; the decision against the
+    oracle's TopK; the full-length result against the states the rows had when they stopped."""
+    N, d, m, L, l_s, theta = 700, 256, 512, 4, 1, 1.0e6
+    cfg = I.LayerConfig("blocks", "bf16", N, N, d, 4, 2, 64, 0.667, seed=70)
+    Wnp = []
+    for l in range(L):
+        w = I.make_projection_weights(cfg, l)
+        w.update(I.make_ffn_weights(cfg, l, m))
+        Wnp.append(w)
+    Wdev = []
+    for w in Wnp:
+        dw = {k: _dev(w[k]) for k in ("w_q", "w_k", "w_v", "w_o", "w_down")}
+        dw["w_gate_up"] = B.interleave_gate_up(_dev(w["w_gate"]), _dev(w["w_up"]))
+        Wdev.append(dw)
+    st = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
+    st.params.keep_first_n, st.params.keep_last_n = 64, 32
+    k_keep = B.keep_count(N, 0.667, 64, 32, paper_impl_rounding=True)
+    assert k_keep == N - round(0.667 * (N - 96))
+    x0 = I.make_hidden(cfg)
+    seen = {}
+
+    def check(l, x_in, idx, n, st_, x_out):
+        xs, idx_np = _f(x_in[:n]), idx[:n].cpu().numpy()
+        W = Wnp[l]
+        oq, ok, ov = ref.rmsnorm_qkv(xs, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                                     pos=idx_np, rope_theta=theta)
+        qs, ks, vs = _f(st_.q[:n]), _f(st_.k[:n]), _f(st_.v[:n])
+        assert P.row_rel_err(qs.reshape(n, -1), oq.reshape(n, -1)).max() <= 2e-2
+        assert P.row_rel_err(ks.reshape(n, -1), ok.reshape(n, -1)).max() <= 2e-2
+        rule = ref.RULE_TOPK if l == l_s else ref.RULE_NONE
+        o = ref.attn_layer(xs, qs, ks, vs, W["w_o"], idx_np, rule=rule, k_keep=k_keep, keep_first_n=64, keep_last_n=32)
+        h_next = ref.ffn_swiglu(o.x_next, W["w_gate"], W["w_up"], W["w_down"])
+        assert P.row_rel_err(_f(x_out[:n]), h_next).max() <= P.X_TOL["bf16"]
+        if l == l_s:
+            halt = st_.buf.halt_mask[:n].cpu().numpy()
+            assert int((halt == 0).sum()) == k_keep == o.n_active_out
+            assert not halt[:64].any() and not halt[-32:].any()                      # App. A's protected ranges
+            thr = np.sort(o.scores[64:n - 32])[::-1][k_keep - 96 - 1]
+            band = np.abs(o.scores - thr) <= P.BAND_REL * thr
+            assert np.array_equal(halt[~band], o.halt[~band])
+            seen.update(halt=halt, state=_f(x_out[:n]).copy(), band=int(band.sum()))
+        seen["last_n"] = n
+
+    res = SS.run_single_shot(st, _dev(x0), Wdev, l_s, k_keep, rope_theta=theta, on_block=check)
+    torch.cuda.synchronize()
+    assert res["n_after"] == k_keep == seen["last_n"]
+    final = _f(res["final"])
+    halt = seen["halt"]
+    # halted tokens: the state they had at the end of block l_s, bit for bit; survivors: the last block's output
+    np.testing.assert_array_equal(final[halt == 1], seen["state"][halt == 1])
+    surv = res["idx"][:k_keep].cpu().numpy()
+    np.testing.assert_array_equal(surv, np.nonzero(halt == 0)[0])
+    last = st.x_a if (L - 1) % 2 == 0 else st.x_b
+    np.testing.assert_array_equal(final[surv], _f(last[:k_keep]))
+    assert not np.array_equal(final[surv], seen["state"][halt == 0])                # they did move on
+    print("single shot: kept", k_keep, "of", N, "band rows", seen["band"])
+
+
+def test_single_shot_without_halting_is_the_plain_model():
+    """l_s = None: every block on every row; the result is the last block's output at every position."""
+    N, d, m, L = 200, 128, 128, 2
+    cfg = I.LayerConfig("blocks_full", "bf16", N, N, d, 2, 1, 64, 0.0, seed=71)
+    Wdev = []
+    for l in range(L):
+        w = I.make_projection_weights(cfg, l)
+        w.update(I.make_ffn_weights(cfg, l, m))
+        dw = {k: _dev(w[k]) for k in ("w_q", "w_k", "w_v", "w_o", "w_down")}
+        dw["w_gate_up"] = B.interleave_gate_up(_dev(w["w_gate"]), _dev(w["w_up"]))
+        Wdev.append(dw)
+    st = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
+    res = SS.run_single_shot(st, _dev(I.make_hidden(cfg)), Wdev, None, N, rope_theta=5.0e5)
+    torch.cuda.synchronize()
+    assert res["n_after"] == N
+    assert torch.equal(res["final"], st.x_b[:N])
