@@ -113,13 +113,83 @@ def run_chain_bench(args, cfg, n_layers=8):
         "layers": layers}))
 
 
+def run_single_shot_bench(args, cfg):
+    """The single-shot schedule of Alg. 1 end to end on synthetic weights, in the setting of the paper's table of
+    theoretical prefill FLOPs (App. A): Qwen2.5-7B shapes, L = 28 blocks, hidden 3584, FFN width 18944, decision
+    after the 11th block, reduction ratio 0.667 with 64 + 32 protected tokens. A step = one whole prefill with
+    halting; the full model (no halting) is timed beside it and the ratio reported next to the paper's analytic
+    one."""
+    import torch
+    from paper_2604_18103_amd import binding as B
+    from paper_2604_18103_amd import inputs as I
+    from paper_2604_18103_amd import single_shot as SS
+
+    L, m, start_block, rho, first, last = 28, 18944, 11, 0.667, 64, 32
+    N, d, dh, Hq, Hkv = cfg.N, cfg.d, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
+    k_keep = B.keep_count(N, rho, first, last, paper_impl_rounding=True)
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    bf = torch.bfloat16
+
+    def rnd(rows, cols, fan):
+        return (torch.randn((rows, cols), generator=g, device="cuda", dtype=torch.float32) * fan ** -0.5).to(bf)
+
+    weights = []
+    for _ in range(L):
+        weights.append(dict(w_q=rnd(d, Hq * dh, d), w_k=rnd(d, Hkv * dh, d), w_v=rnd(d, Hkv * dh, d),
+                            w_o=rnd(Hq * dh, d, d), w_down=rnd(m, d, m),
+                            w_gate_up=B.interleave_gate_up(rnd(d, m, d), rnd(d, m, d))))
+    x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)
+    st = SS.alloc_blocks(d, Hq, Hkv, dh, m, N)
+    st.params.keep_first_n, st.params.keep_last_n = first, last
+    final = torch.empty_like(x0)
+
+    def timed(l_s, reps, warm):
+        for _ in range(warm):
+            SS.run_single_shot(st, x0, weights, l_s, k_keep, rope_theta=1.0e6, final=final)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            res = SS.run_single_shot(st, x0, weights, l_s, k_keep, rope_theta=1.0e6, final=final)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps, res
+
+    t_dash, res = timed(start_block - 1, args.steps, max(1, args.warmup))
+    assert res["n_after"] == k_keep
+    t_full, _ = timed(None, max(2, args.steps // 4), 1)
+
+    def block_flops(n):   # what the kernels execute: causal attention, GQA projections, three FFN matrices
+        return (attention_flops(cfg, n) + wo_flops(cfg, n) + 2.0 * n * d * (Hq + 2 * Hkv) * dh + 6.0 * n * d * m)
+
+    def paper_A(n):       # App. A: A(n) = 4 n d^2 + 2 n^2 d + 2 n d m
+        return 4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m
+
+    flops_full = L * block_flops(N)
+    flops_dash = start_block * block_flops(N) + (L - start_block) * block_flops(k_keep)
+    print(json.dumps({
+        "metric": "prompt tokens/s of a 28-block prefill with single-shot halting after block 11 "
+                  "(Qwen2.5-7B shapes, N=32768, 66.7 % of the unprotected tokens halted)",
+        "value": N / t_dash, "unit": "prompt tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t_dash, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "qwen_32k_single_shot", "N": N, "blocks": L, "start_block": start_block,
+                   "reduction_ratio": rho, "protected": [first, last], "n_kept": k_keep, "hidden": d, "ffn": m,
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": dh, "rope_theta": 1.0e6},
+        "full_model_ms": 1e3 * t_full, "speedup_vs_full_model": t_full / t_dash,
+        "speedup_of_executed_flops": flops_full / flops_dash,
+        "speedup_paper_formula": L * paper_A(N) / (start_block * paper_A(N) + (L - start_block) * paper_A(k_keep)),
+        "roofline": {"bound": "mfma", "achieved": flops_dash / t_dash / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": flops_dash / t_dash / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "full_model_tflops": flops_full / t_full / 1e12}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_32k_half",
-                    help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads)")
+                    help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads; qwen_32k_chain is "
+                         "the 8-layer chain), or qwen_32k_single_shot (28 full blocks, one halting decision)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run device-to-device copies of this many MiB (a plain copy kernel of known "
@@ -139,6 +209,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()  # fail loudly if the HIP library is missing
+    if args.workload == "qwen_32k_single_shot":
+        run_single_shot_bench(args, I.CONFIGS["qwen_32k_chain"])
+        return
     cfg = I.CONFIGS[args.workload]
     if args.workload == "qwen_32k_chain":
         run_chain_bench(args, cfg)
