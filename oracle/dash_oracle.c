@@ -31,6 +31,7 @@
  *                          divided by ||H_t||_2 (the "relative" form of Fig. 1)
  *   - decide_topk        : S* = TopK(S, K, Delta)      (Eq. 3): keep high, halt low
  *   - decide_threshold   : the threshold-line form of the same cut (Fig. 8)
+ *   - decide_topk_keep_low : the direction control of Sec. 5.4 (high-Delta tokens halt)
  *   - compact            : gather rows by the surviving index set
  *                          (Alg. 1 step 4, Sec. 3.4)
  *   - keep_count         : K = floor((1-rho) T) (Eq. 3) and the kept length
@@ -338,6 +339,44 @@ int dash_oracle_decide_topk(const double *scores, int64_t n, int64_t k_keep, int
         }
     }
     qsort(cand, (size_t)n_cand, sizeof(scored_row), by_score_desc_then_row);
+    int64_t quota = k_keep - n_prot;
+    if (quota < 0) quota = 0;
+    if (quota > n_cand) quota = n_cand;
+    for (int64_t c = 0; c < quota; ++c) halt[cand[c].i] = 0;
+    free(cand);
+    return 0;
+}
+
+static int by_score_asc_then_row(const void *a, const void *b) {
+    const scored_row *x = (const scored_row *)a, *y = (const scored_row *)b;
+    if (x->s < y->s) return -1;
+    if (x->s > y->s) return 1;
+    return (x->i > y->i) - (x->i < y->i);
+}
+
+/*
+ * The direction control of the ablation (Sec. 5.4, "Directionality"): same budget, but the rows with the LOWEST
+ * scores are kept, i.e. the high-Delta tokens halt. Everything else as in dash_oracle_decide_topk. (Random
+ * halting, the other control, is the ordinary TopK on scores drawn at random by the caller.)
+ */
+int dash_oracle_decide_topk_keep_low(const double *scores, int64_t n, int64_t k_keep, int64_t n_first,
+                                     int64_t n_last, uint8_t *halt) {
+    if (!scores || !halt || n < 0 || k_keep < 0 || n_first < 0 || n_last < 0) return -1;
+    scored_row *cand = (scored_row *)malloc((size_t)(n > 0 ? n : 1) * sizeof(scored_row));
+    if (!cand) return -2;
+    int64_t n_cand = 0, n_prot = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (row_is_protected(i, n, n_first, n_last)) {
+            halt[i] = 0;
+            ++n_prot;
+        } else {
+            halt[i] = 1;
+            cand[n_cand].s = scores[i];
+            cand[n_cand].i = i;
+            ++n_cand;
+        }
+    }
+    qsort(cand, (size_t)n_cand, sizeof(scored_row), by_score_asc_then_row);
     int64_t quota = k_keep - n_prot;
     if (quota < 0) quota = 0;
     if (quota > n_cand) quota = n_cand;

@@ -52,6 +52,7 @@ def _load():
     lib.dash_oracle_scores.argtypes = [dp, dp, C.c_int64, C.c_int32, C.c_int32, dp]
     lib.dash_oracle_decide_threshold.argtypes = [dp, C.c_int64, C.c_double, C.c_int64, C.c_int64, u8p]
     lib.dash_oracle_decide_topk.argtypes = [dp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, u8p]
+    lib.dash_oracle_decide_topk_keep_low.argtypes = [dp, C.c_int64, C.c_int64, C.c_int64, C.c_int64, u8p]
     lib.dash_oracle_compact.argtypes = [u8p, i32p, dp, C.c_int64, C.c_int32, i32p, dp, i64p]
     lib.dash_oracle_keep_count.argtypes = [C.c_int64, C.c_double, C.c_int64, C.c_int64, C.c_int32]
     lib.dash_oracle_keep_count.restype = C.c_int64
@@ -209,13 +210,21 @@ def decide_threshold(s, tau, keep_first_n=0, keep_last_n=0) -> np.ndarray:
     return halt
 
 
-def decide_topk(s, k_keep, keep_first_n=0, keep_last_n=0) -> np.ndarray:
+def decide_topk(s, k_keep, keep_first_n=0, keep_last_n=0, keep_low=False) -> np.ndarray:
+    """Eq. 3; keep_low=True is the direction control of Sec. 5.4 (the K LOWEST scores are kept)."""
     s = _f64(s)
     halt = np.empty((s.shape[0],), dtype=np.uint8)
-    _check(_load().dash_oracle_decide_topk(_ptr(s, C.c_double), s.shape[0], int(k_keep),
-                                           int(keep_first_n), int(keep_last_n),
-                                           _ptr(halt, C.c_uint8)), "decide_topk")
+    fn = _load().dash_oracle_decide_topk_keep_low if keep_low else _load().dash_oracle_decide_topk
+    _check(fn(_ptr(s, C.c_double), s.shape[0], int(k_keep), int(keep_first_n), int(keep_last_n),
+              _ptr(halt, C.c_uint8)), "decide_topk")
     return halt
+
+
+def score_block(x_new, x_old, kind=SCORE_REL) -> np.ndarray:
+    """The block-level signal of the ablation (Sec. 5.4): Eq. 2 applied to the change of the representation
+    across the whole block, ||H^(l+1)_t - H^(l)_t||_2, optionally relative to ||H^(l)_t||_2."""
+    x_new, x_old = _f64(x_new), _f64(x_old)
+    return scores(x_new - x_old, x_old, kind)
 
 
 def compact(halt, active_idx, x_next=None):

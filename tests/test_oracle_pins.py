@@ -487,3 +487,37 @@ def test_scatter_rows_writes_selected_rows_at_original_positions():
     assert np.array_equal(out0[[1, 4, 5, 9]], rows)
     with pytest.raises(Exception):
         ref.scatter_rows(rows, np.array([1, 4, 5, 10], dtype=np.int32), full)
+
+
+# ---------------------------------------------------------------- signal and direction variants (Sec. 5.4)
+
+def test_topk_keep_low_hand_vectors_and_complement():
+    s = np.array([0.5, 0.1, 0.9, 0.1, 0.7, 0.3])
+    # keep the 3 lowest: 0.1 (row 1), 0.1 (row 3), 0.3 (row 5)
+    np.testing.assert_array_equal(ref.decide_topk(s, 3, keep_low=True), [1, 0, 1, 0, 1, 0])
+    # ties: the earlier row is kept first
+    np.testing.assert_array_equal(ref.decide_topk(s, 1, keep_low=True), [1, 0, 1, 1, 1, 1])
+    # protected rows count towards the budget and never halt
+    np.testing.assert_array_equal(ref.decide_topk(s, 3, keep_first_n=1, keep_last_n=1, keep_low=True), [0, 0, 1, 1, 1, 0])
+    np.testing.assert_array_equal(ref.decide_topk(s, 0, keep_low=True), [1] * 6)
+    np.testing.assert_array_equal(ref.decide_topk(s, 6, keep_low=True), [0] * 6)
+    # without ties: the rows kept when keeping the K lowest are exactly the rows halted when keeping the n-K highest
+    rng = np.random.default_rng(80)
+    r = rng.permutation(200).astype(np.float64)
+    for K in (0, 1, 57, 199, 200):
+        low = ref.decide_topk(r, K, keep_low=True)
+        high = ref.decide_topk(r, 200 - K)
+        np.testing.assert_array_equal(low, 1 - high)
+    # negating the scores turns one rule into the other (no ties here)
+    np.testing.assert_array_equal(ref.decide_topk(-r, 57, keep_low=True), ref.decide_topk(r, 57))
+
+
+def test_score_block_is_eq2_on_the_block_change():
+    rng = np.random.default_rng(81)
+    a, b = rng.standard_normal((5, 7)), rng.standard_normal((5, 7))
+    np.testing.assert_allclose(ref.score_block(b, a, ref.SCORE_ABS), np.linalg.norm(b - a, axis=1), rtol=1e-14)
+    np.testing.assert_allclose(ref.score_block(b, a), np.linalg.norm(b - a, axis=1) / np.linalg.norm(a, axis=1), rtol=1e-14)
+    assert np.all(ref.score_block(a, a) == 0.0)
+    # a block that only adds the attention output has block signal == attention signal
+    u = rng.standard_normal((5, 7))
+    np.testing.assert_allclose(ref.score_block(a + u, a), ref.scores(u, a), rtol=1e-12)
