@@ -151,6 +151,19 @@ dash_status dash_compact(const dash_layer_params *params, const uint8_t *halt_ma
 dash_status dash_score_rows(const float *delta, const void *x, int32_t n, int32_t d, int32_t dtype,
                             int32_t score_kind, float *scores, void *hip_stream);
 
+/* Variants of the ablation (Sec. 5.4), built from the same decision and compaction kernels:
+ *  - dash_score_diff_rows: the block-level signal, Eq. 2 applied to the change of a row across a whole block,
+ *    ||x_new_t - x_old_t||_2 [/ ||x_old_t||_2] (x_new, x_old: device [n,d] in dtype; one pass over HBM).
+ *  - dash_decide_topk: the TopK decision of Eq. 3 on scores the caller provides (device fp32 [n]): any signal,
+ *    or random numbers for the random-halting control. keep_low != 0 keeps the K LOWEST scores instead (the
+ *    high-Delta tokens halt: the direction control). K, rho and the protected ranges come from params as for
+ *    DASH_RULE_TOPK; ties keep the earlier row. Outputs and workspace as in dash_score_decide. */
+dash_status dash_score_diff_rows(const void *x_new, const void *x_old, int32_t n, int32_t d, int32_t dtype,
+                                 int32_t score_kind, float *scores, void *hip_stream);
+dash_status dash_decide_topk(const dash_layer_params *params, const float *scores, int32_t n, int32_t keep_low,
+                             uint8_t *halt_mask, int32_t *chunk_keep_counts, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
+
 /* Front end of a layer in a chain (Eq. 1's LN and the q/k/v projections, which sit before the path):
  * h = x / sqrt(mean(x^2) + 1e-6) (unit gain); q = h @ w_q [d, Hq*dh]; k = h @ w_k; v = h @ w_v
  * [d, Hkv*dh]. bf16 only. h_scratch: device [n,d] bf16. */

@@ -74,13 +74,15 @@ def lib() -> C.CDLL:
     L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp]
     L.dash_rope_qk.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_double, _vp]
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
+    L.dash_score_diff_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
+    L.dash_decide_topk.argtypes = [pp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp]
     L.dash_ffn_workspace_bytes.restype = C.c_size_t
     L.dash_ffn_workspace_bytes.argtypes = [pp, C.c_int32, C.c_int32]
     L.dash_ffn_swiglu.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]
     L.dash_scatter_rows.argtypes = [_vp, _vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     for name in ("dash_attn_layer", "dash_flash_fwd", "dash_wo_residual_rownorm", "dash_score_decide",
                  "dash_compact", "dash_score_rows", "dash_rmsnorm_qkv", "dash_rope_qk", "dash_validate_active_idx",
-                 "dash_profile_read", "dash_ffn_swiglu", "dash_scatter_rows"):
+                 "dash_profile_read", "dash_ffn_swiglu", "dash_scatter_rows", "dash_score_diff_rows", "dash_decide_topk"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -226,6 +228,17 @@ def dash_compact(params, halt_mask, chunk_keep_counts, active_idx, x_next, n, x_
 def dash_score_rows(delta, x, n, d, dtype, score_kind, scores) -> None:
     _check(lib().dash_score_rows(_p(delta), _p(x), int(n), int(d), int(dtype), int(score_kind), _p(scores),
                                  _stream()), "dash_score_rows")
+
+
+def dash_score_diff_rows(x_new, x_old, n, d, dtype, score_kind, scores) -> None:
+    _check(lib().dash_score_diff_rows(_p(x_new), _p(x_old), int(n), int(d), int(dtype), int(score_kind), _p(scores),
+                                      _stream()), "dash_score_diff_rows")
+
+
+def dash_decide_topk(params, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace) -> None:
+    _check(lib().dash_decide_topk(C.byref(params), _p(scores), int(n), int(bool(keep_low)), _p(halt_mask),
+                                  _p(chunk_keep_counts), _p(workspace), workspace.numel(), _stream()),
+           "dash_decide_topk")
 
 
 def ffn_workspace_bytes(params: LayerParams, n_capacity: int, m: int) -> int:

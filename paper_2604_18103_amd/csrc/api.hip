@@ -168,6 +168,30 @@ dash_status dash_score_decide(const dash_layer_params* p, const float* norm_part
                                halt_mask, chunk_keep_counts, workspace, (hipStream_t)hip_stream);
 }
 
+dash_status dash_decide_topk(const dash_layer_params* p, const float* scores, int32_t n, int32_t keep_low,
+                             uint8_t* halt_mask, int32_t* chunk_keep_counts, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!scores || !halt_mask || !chunk_keep_counts) return DASH_ERR_INVALID_ARG;
+    const size_t need = decide_workspace_bytes() + (size_t)((n + kChunkRows - 1) / kChunkRows) * 4;
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DASH_ERR_WORKSPACE;
+    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace,
+                              (hipStream_t)hip_stream);
+}
+
+dash_status dash_score_diff_rows(const void* x_new, const void* x_old, int32_t n, int32_t d, int32_t dtype,
+                                 int32_t score_kind, float* scores, void* hip_stream) {
+    if (n < 0 || d <= 0 || (dtype != DASH_BF16 && dtype != DASH_F32)) return DASH_ERR_INVALID_ARG;
+    if (score_kind != DASH_SCORE_REL && score_kind != DASH_SCORE_ABS) return DASH_ERR_INVALID_ARG;
+    if (d % (dtype == DASH_BF16 ? 8 : 4) != 0) return DASH_ERR_UNSUPPORTED;
+    if (n == 0) return DASH_OK;
+    if (!x_new || !x_old || !scores || !aligned16(x_new) || !aligned16(x_old)) return DASH_ERR_INVALID_ARG;
+    return launch_score_diff_rows(x_new, x_old, n, d, dtype, score_kind, scores, (hipStream_t)hip_stream);
+}
+
 dash_status dash_compact(const dash_layer_params* p, const uint8_t* halt_mask,
                          const int32_t* chunk_keep_counts, const int32_t* active_idx, const void* x_next,
                          int32_t n, void* x_compact, int32_t* new_active_idx, int32_t* n_active_out,

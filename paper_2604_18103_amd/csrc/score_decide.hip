@@ -77,6 +77,13 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
+// Key under which TopK ranks a score: the order-preserving key, or its complement when the rows with the
+// LOWEST scores are to be kept (the direction control of Sec. 5.4).
+__device__ __forceinline__ uint32_t rank_key(float f, int keep_low) {
+    const uint32_t k = order_key(f);
+    return keep_low ? ~k : k;
+}
+
 struct TopkState {
     uint32_t threshold_key;  // key of the K-th largest candidate score
     int32_t tie_quota;       // how many rows with exactly that key are kept (earliest rows first)
@@ -88,8 +95,8 @@ constexpr int kSelectThreads = 1024;
 // unprotected rows by four 8-bit radix passes (integer histograms in LDS), then counts, per 64-row
 // chunk, the rows that tie with it, so the flag kernel can keep the earliest ties first.
 __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
-    const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, TopkState* __restrict__ st,
-    int32_t* __restrict__ tie_counts) {
+    const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, int keep_low,
+    TopkState* __restrict__ st, int32_t* __restrict__ tie_counts) {
     __shared__ int hist[256];
     __shared__ uint32_t sh_prefix;
     __shared__ int sh_remaining;
@@ -120,7 +127,7 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
         const uint32_t prefix = sh_prefix;
         const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
         for (int r = lo + tid; r < hi; r += kSelectThreads) {
-            const uint32_t key = order_key(scores[r]);
+            const uint32_t key = rank_key(scores[r], keep_low);
             if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFFu], 1);
         }
         __syncthreads();
@@ -146,7 +153,7 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
     for (int c = wave; c < n_chunks; c += kSelectThreads / kWave) {
         const int row = c * kChunkRows + lane;
-        const bool tie = row >= lo && row < hi && order_key(scores[row]) == T;
+        const bool tie = row >= lo && row < hi && rank_key(scores[row], keep_low) == T;
         const unsigned long long m = __ballot(tie);
         if (lane == 0) tie_counts[c] = __popcll(m);
     }
@@ -154,7 +161,8 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
 
 // TopK flags: keep protected rows, rows above the threshold key, and the first tie_quota rows equal to it.
 __global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict__ scores, int n, int n_first,
-                                                        int n_last, const TopkState* __restrict__ st,
+                                                        int n_last, int keep_low,
+                                                        const TopkState* __restrict__ st,
                                                         const int32_t* __restrict__ tie_counts,
                                                         uint8_t* __restrict__ halt,
                                                         int32_t* __restrict__ chunk_counts) {
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict_
         if (row_protected(row, n, n_first, n_last)) {
             keep = true;
         } else {
-            const uint32_t key = order_key(scores[row]);
+            const uint32_t key = rank_key(scores[row], keep_low);
             keep = key > T;
             tie = key == T;
         }
@@ -243,9 +251,74 @@ dash_status launch_score_decide(const dash_layer_params& p, const float* partial
     hipLaunchKernelGGL(score_only_kernel, dim3(blocks), dim3(256), 0, s, partials, n_partials, n,
                        p.score_kind, scores);
     hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, (int)k_keep, st, tie_counts);
+                       p.keep_last_n, (int)k_keep, 0, st, tie_counts);
     hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, st, tie_counts, halt, chunk_counts);
+                       p.keep_last_n, 0, st, tie_counts, halt, chunk_counts);
+    return launch_status();
+}
+
+// TopK decision on scores the caller provides (any signal: the block-level one, random numbers for the random
+// control); keep_low selects the direction control.
+dash_status launch_decide_topk(const dash_layer_params& p, const float* scores, int n, int keep_low, uint8_t* halt,
+                               int32_t* chunk_counts, void* ws, hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    int64_t k_keep = p.k_keep;
+    if (k_keep < 0) k_keep = dash_keep_count(n, (double)p.rho, 0, 0, 0);
+    if (k_keep > n) k_keep = n;
+    TopkState* st = reinterpret_cast<TopkState*>(ws);
+    int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
+    const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
+    hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, p.keep_first_n,
+                       p.keep_last_n, (int)k_keep, keep_low ? 1 : 0, st, tie_counts);
+    hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, p.keep_first_n,
+                       p.keep_last_n, keep_low ? 1 : 0, st, tie_counts, halt, chunk_counts);
+    return launch_status();
+}
+
+// Block-level signal of the ablation (Sec. 5.4): Eq. 2 on the change of a row across a whole block,
+// ||x_new - x_old||_2, optionally relative to ||x_old||_2. One wave per row, 16-byte loads, two reads per element.
+template <typename T>
+__global__ __launch_bounds__(256) void score_diff_rows_kernel(const T* __restrict__ x_new, const T* __restrict__ x_old,
+                                                              int n, int d, int kind, float* __restrict__ scores) {
+    constexpr int VEC = 16 / (int)sizeof(T);
+    const int row = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) / kWave);
+    const int lane = threadIdx.x % kWave;
+    if (row >= n) return;
+    const T* a = x_new + (size_t)row * d;
+    const T* b = x_old + (size_t)row * d;
+    float sd = 0.f, sx = 0.f;
+    for (int c = lane * VEC; c < d; c += kWave * VEC) {  // d % VEC == 0 is checked by the caller
+        T va[VEC], vb[VEC];
+        *reinterpret_cast<u32x4*>(va) = *reinterpret_cast<const u32x4*>(a + c);
+        *reinterpret_cast<u32x4*>(vb) = *reinterpret_cast<const u32x4*>(b + c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float o = to_float(vb[e]), df = to_float(va[e]) - o;
+            sd = fmaf(df, df, sd);
+            sx = fmaf(o, o, sx);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        sd += __shfl_xor(sd, o);
+        sx += __shfl_xor(sx, o);
+    }
+    if (lane == 0) {
+        const float nd = sqrtf(sd);
+        scores[row] = kind == DASH_SCORE_ABS ? nd : nd / fmaxf(sqrtf(sx), kNormEps);
+    }
+}
+
+dash_status launch_score_diff_rows(const void* x_new, const void* x_old, int n, int d, int dtype, int kind,
+                                   float* scores, hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
+    if (dtype == DASH_BF16)
+        hipLaunchKernelGGL(score_diff_rows_kernel<__bf16>, dim3(blocks), dim3(256), 0, s, (const __bf16*)x_new,
+                           (const __bf16*)x_old, n, d, kind, scores);
+    else
+        hipLaunchKernelGGL(score_diff_rows_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)x_new,
+                           (const float*)x_old, n, d, kind, scores);
     return launch_status();
 }
 

@@ -148,3 +148,55 @@ def test_single_shot_without_halting_is_the_plain_model():
     torch.cuda.synchronize()
     assert res["n_after"] == N
     assert torch.equal(res["final"], st.x_b[:N])
+
+
+# ---------------------------------------------------------------- signal and direction variants (Sec. 5.4)
+
+@pytest.mark.parametrize("n", [1, 63, 64, 1000, 4097])
+def test_decide_topk_on_given_scores_both_directions(n):
+    """TopK on caller-provided scores: integer work, compared bit for bit. Random scores are the random-halting
+    control; keep_low is the high-Delta control. Heavy ties included."""
+    rng = np.random.default_rng(90 + n)
+    p = B.make_params(256, 4, 2, 64)
+    ws = torch.empty((256 + 4 * ((n + 63) // 64) + 64,), dtype=torch.uint8, device="cuda")
+    for case in range(6):
+        s = rng.random(n).astype(np.float32)
+        if case % 2:
+            s = np.round(s * 7) / 7                      # many exact ties
+        if case == 4:
+            s = -s
+        first, last = ((0, 0), (3, 2), (64, 32))[case % 3]
+        k_keep = int(rng.integers(0, n + 1))
+        p.k_keep, p.keep_first_n, p.keep_last_n = k_keep, first, last
+        gs = torch.from_numpy(s).cuda()
+        for keep_low in (False, True):
+            halt = torch.empty((n,), dtype=torch.uint8, device="cuda")
+            counts = torch.empty(((n + 63) // 64,), dtype=torch.int32, device="cuda")
+            B.dash_decide_topk(p, gs, n, keep_low, halt, counts, ws)
+            torch.cuda.synchronize()
+            want = ref.decide_topk(s.astype(np.float64), k_keep, first, last, keep_low=keep_low)
+            np.testing.assert_array_equal(halt.cpu().numpy(), want)
+            kept = (want == 0).astype(np.int64)
+            np.testing.assert_array_equal(counts.cpu().numpy(), np.add.reduceat(kept, np.arange(0, n, 64)))
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_score_diff_rows_matches_oracle(dt):
+    n, d = 333, 512
+    rng = np.random.default_rng(95)
+    a = rng.standard_normal((n, d)) * np.exp(rng.standard_normal((n, 1)))
+    b = a + 0.05 * rng.standard_normal((n, d)) * np.abs(a).mean(1, keepdims=True)
+    b[7] = a[7]
+    if dt == "bf16":
+        a, b = I.round_to_bf16(a), I.round_to_bf16(b)
+    else:
+        a, b = a.astype(np.float32).astype(np.float64), b.astype(np.float32).astype(np.float64)
+    code = B.DASH_BF16 if dt == "bf16" else B.DASH_F32
+    ga, gb = B.to_device(a, code), B.to_device(b, code)
+    for kind in (ref.SCORE_REL, ref.SCORE_ABS):
+        out = torch.empty((n,), dtype=torch.float32, device="cuda")
+        B.dash_score_diff_rows(gb, ga, n, d, code, kind, out)
+        torch.cuda.synchronize()
+        want = ref.score_block(b, a, kind)
+        np.testing.assert_allclose(out.cpu().numpy(), want, rtol=2e-5, atol=1e-30)
+        assert out[7].item() == 0.0
