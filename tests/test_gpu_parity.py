@@ -42,6 +42,19 @@ def test_bf16_head_layouts(heads):
     print(cfg.name, rep)
 
 
+@pytest.mark.parametrize("halt_frac", [0.75, 0.9, 0.99, 0.999])
+def test_extreme_reduction_ratios(halt_frac):
+    """The aggressive budgets of the vision-language setting (Sec. 4.3: up to 99 % of the tokens dropped): the
+    decision, the counts and the compaction with very few survivors, threshold and TopK alike."""
+    cfg = I.scaled(NARROW, 1333, N=4000, halt_frac=halt_frac)
+    rep, g, o = P.full_parity(cfg)
+    assert g.n_active_out == o.n_active_out or rep["band_rows"] > 0
+    assert o.n_active_out <= int(round((1 - halt_frac) * cfg.n)) + 1
+    rep2, g2, o2 = P.full_parity(cfg, rule=B.RULE_TOPK)
+    assert g2.n_active_out == o2.n_active_out == cfg.n - int(halt_frac * cfg.n)
+    print(cfg.name, halt_frac, rep, rep2)
+
+
 def test_bf16_qwen_shape_ragged():
     """Qwen2.5-7B layer shape (hidden 3584, 28/4 heads, head_dim 128) at a length that is not a
     multiple of any tile (query tile 128, key tile 64, GEMM tile 256)."""
