@@ -110,7 +110,7 @@ constexpr int kGThreads = 512;
 constexpr int kGAElems = kGM * kGK, kGBElems = kGK * kGN;
 constexpr int kGStageElems = kGAElems + kGBElems;
 constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (131072 B)
-constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row
+constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row (conflict-free 16-byte reads of two rows by 16 lanes)
 static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float), "epilogue staging must fit");
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
