@@ -265,6 +265,39 @@ def flops_reduction_and_speedup(n, n_hat, d, m, L, l_s):
     return 1.0 - ours / full, full / ours
 
 
+def schedule_lengths(n, L, shots, n_first=0, n_last=0):
+    """Sequence length each of the L blocks runs on when halting decisions are taken at several blocks.
+    `shots` maps a block index to the compression ratio c applied to the rows that enter that block: the block
+    itself still runs on all of them (Alg. 1 takes the decision after the block's FFN) and the blocks after it on
+    the kept ones, whose number follows App. A's rule on the current length (protected first/last ranks in the
+    current order). One entry at l_s is the single-shot schedule of Alg. 1."""
+    lengths, cur = [], int(n)
+    for l in range(int(L)):
+        lengths.append(cur)
+        if l in shots:
+            cur = keep_count(cur, shots[l], n_first, n_last, paper_impl_rounding=True)
+    return lengths
+
+
+def schedule_flops(lengths, d, m) -> float:
+    """Prefill FLOPs of a schedule under the per-block proxy A of App. A: the sum of A over the blocks' lengths
+    (for one shot at l_s this is l_s A(n) + (L - l_s) A(n_hat))."""
+    return float(sum(flops_A(t, d, m) for t in lengths))
+
+
+def comparable_multi_shot_ratio(n, L, shot_layers, target_flops, d, m, n_first=0, n_last=0, grid=10000):
+    """Per-shot compression ratio of a multi-shot schedule with a budget comparable to a single-shot one
+    (App. D compares them under comparable pruning budgets without saying how the budget is split; reading:
+    every shot uses the same ratio c, a multiple of 1/grid, and c is the smallest one whose schedule costs no
+    more than `target_flops`). Plain scan over the grid."""
+    for i in range(grid + 1):
+        c = i / grid
+        lengths = schedule_lengths(n, L, {l: c for l in shot_layers}, n_first, n_last)
+        if schedule_flops(lengths, d, m) <= target_flops:
+            return c
+    raise ValueError("no ratio on the grid meets the budget")
+
+
 @dataclass
 class LayerResult:
     rows: np.ndarray          # query rows that were evaluated (indices into the active order)

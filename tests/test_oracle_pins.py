@@ -335,6 +335,44 @@ def test_eq3_keep_count_is_floor():
     assert ref.keep_count(16384, 0.667) == math.floor((1 - 0.667) * 16384)
 
 
+def test_schedule_lengths_and_cost_reduce_to_single_shot_table5():
+    """One shot at l_s = 11 of 28 blocks: 11 blocks at n, 17 at n_hat, and the cost ratio is Table 5's speedup."""
+    for n, n_hat, r_pct, s in _table5():
+        lengths = ref.schedule_lengths(n, 28, {11: 0.667}, 64, 32)
+        assert lengths == [n] * 12 + [n_hat] * 16       # block 11 itself still runs on all n rows ...
+        # ... while App. A's count charges blocks l_s..L-1 at n_hat (17 reduced blocks): its cost is the
+        # schedule's with the decision taken one block earlier
+        cost_app_a = ref.schedule_flops(ref.schedule_lengths(n, 28, {10: 0.667}, 64, 32), 3584, 18944)
+        full = ref.schedule_flops([n] * 28, 3584, 18944)
+        assert abs(full / cost_app_a - s) < 0.006
+        assert abs(100.0 * (1.0 - cost_app_a / full) - r_pct) < 0.006
+
+
+def test_schedule_lengths_multi_shot_by_hand():
+    # 100 rows, ratio 0.5 at blocks 1 and 3, 4 + 2 protected: drop round(0.5 * 94) = 47 -> 53; then
+    # drop round(0.5 * 47) = 24 (23.5 rounds half away from zero) -> 29
+    assert ref.schedule_lengths(100, 5, {1: 0.5, 3: 0.5}, 4, 2) == [100, 100, 53, 53, 29]
+    assert ref.schedule_lengths(100, 3, {}, 4, 2) == [100, 100, 100]
+    assert ref.schedule_lengths(5, 3, {0: 0.9}, 4, 2) == [5, 5, 5]          # nothing outside the protected ranks
+    assert ref.schedule_flops([2, 1], 3, 5) == ref.flops_A(2, 3, 5) + ref.flops_A(1, 3, 5)
+
+
+def test_comparable_multi_shot_ratio_properties():
+    n, L, d, m = 32768, 28, 3584, 18944
+    single = ref.schedule_flops(ref.schedule_lengths(n, L, {11: 0.667}, 64, 32), d, m)
+    # one shot at the same block: the ratio itself comes back
+    assert ref.comparable_multi_shot_ratio(n, L, [11], single, d, m, 64, 32) == 0.667
+    for layers in ([11, 19], [11, 16, 22], [11, 15, 19, 23]):
+        c = ref.comparable_multi_shot_ratio(n, L, layers, single, d, m, 64, 32)
+        lengths = ref.schedule_lengths(n, L, {l: c for l in layers}, 64, 32)
+        assert ref.schedule_flops(lengths, d, m) <= single
+        less = ref.schedule_lengths(n, L, {l: c - 1e-4 for l in layers}, 64, 32)
+        assert ref.schedule_flops(less, d, m) > single                       # the smallest ratio on the grid
+        assert 0.0 < c < 0.667                                               # each shot prunes less than the one shot
+        assert lengths[-1] < 10976                                           # ... but ends shorter (n_hat of one shot)
+        assert all(a >= b for a, b in zip(lengths, lengths[1:]))
+
+
 # ---------------------------------------------------------------- chain front end (LN of Eq. 1)
 
 def test_rmsnorm_closed_forms():
