@@ -113,20 +113,19 @@ def run_chain_bench(args, cfg, n_layers=8):
         "layers": layers}))
 
 
-def run_single_shot_bench(args, cfg):
-    """The single-shot schedule of Alg. 1 end to end on synthetic weights, in the setting of the paper's table of
-    theoretical prefill FLOPs (App. A): Qwen2.5-7B shapes, L = 28 blocks, hidden 3584, FFN width 18944, decision
-    after the 11th block, reduction ratio 0.667 with 64 + 32 protected tokens. A step = one whole prefill with
-    halting; the full model (no halting) is timed beside it and the ratio reported next to the paper's analytic
-    one."""
+QWEN_BLOCKS = dict(L=28, m=18944, start_block=11, first=64, last=32, rope_theta=1.0e6)   # App. A's setting
+
+
+def _blocks_setup(cfg):
+    """Synthetic weights of 28 Qwen2.5-7B-shaped blocks (generated on the device), the prompt's hidden rows and
+    the buffers of the schedule driver."""
     import torch
     from paper_2604_18103_amd import binding as B
     from paper_2604_18103_amd import inputs as I
     from paper_2604_18103_amd import single_shot as SS
 
-    L, m, start_block, rho, first, last = 28, 18944, 11, 0.667, 64, 32
+    L, m = QWEN_BLOCKS["L"], QWEN_BLOCKS["m"]
     N, d, dh, Hq, Hkv = cfg.N, cfg.d, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
-    k_keep = B.keep_count(N, rho, first, last, paper_impl_rounding=True)
     g = torch.Generator(device="cuda").manual_seed(cfg.seed)
     bf = torch.bfloat16
 
@@ -140,29 +139,44 @@ def run_single_shot_bench(args, cfg):
                             w_gate_up=B.interleave_gate_up(rnd(d, m, d), rnd(d, m, d))))
     x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)
     st = SS.alloc_blocks(d, Hq, Hkv, dh, m, N)
-    st.params.keep_first_n, st.params.keep_last_n = first, last
+    st.params.keep_first_n, st.params.keep_last_n = QWEN_BLOCKS["first"], QWEN_BLOCKS["last"]
     final = torch.empty_like(x0)
 
-    def timed(l_s, reps, warm):
+    def timed(shots, reps, warm):
+        """Mean seconds of one prefill under the schedule `shots` {block: rows kept after it}."""
         for _ in range(warm):
-            SS.run_single_shot(st, x0, weights, l_s, k_keep, rope_theta=1.0e6, final=final)
+            SS.run_schedule(st, x0, weights, shots, rope_theta=QWEN_BLOCKS["rope_theta"], final=final)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(reps):
-            res = SS.run_single_shot(st, x0, weights, l_s, k_keep, rope_theta=1.0e6, final=final)
+            res = SS.run_schedule(st, x0, weights, shots, rope_theta=QWEN_BLOCKS["rope_theta"], final=final)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps, res
-
-    t_dash, res = timed(start_block - 1, args.steps, max(1, args.warmup))
-    assert res["n_after"] == k_keep
-    t_full, _ = timed(None, max(2, args.steps // 4), 1)
 
     def block_flops(n):   # what the kernels execute: causal attention, GQA projections, three FFN matrices
         return (attention_flops(cfg, n) + wo_flops(cfg, n) + 2.0 * n * d * (Hq + 2 * Hkv) * dh + 6.0 * n * d * m)
 
-    def paper_A(n):       # App. A: A(n) = 4 n d^2 + 2 n^2 d + 2 n d m
-        return 4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m
+    return timed, block_flops
 
+
+def run_single_shot_bench(args, cfg):
+    """The single-shot schedule of Alg. 1 end to end on synthetic weights, in the setting of the paper's table of
+    theoretical prefill FLOPs (App. A): Qwen2.5-7B shapes, L = 28 blocks, hidden 3584, FFN width 18944, decision
+    after the 11th block, reduction ratio 0.667 with 64 + 32 protected tokens. A step = one whole prefill with
+    halting; the full model (no halting) is timed beside it and the ratio reported next to the paper's analytic
+    one."""
+    from paper_2604_18103_amd import binding as B
+    from paper_2604_18103_amd import single_shot as SS
+
+    L, m, start_block, first, last = (QWEN_BLOCKS[k] for k in ("L", "m", "start_block", "first", "last"))
+    rho = 0.667
+    N, d, dh, Hq, Hkv = cfg.N, cfg.d, cfg.head_dim, cfg.n_q_heads, cfg.n_kv_heads
+    k_keep = B.keep_count(N, rho, first, last, paper_impl_rounding=True)
+    timed, block_flops = _blocks_setup(cfg)
+    t_dash, res = timed({start_block - 1: k_keep}, args.steps, max(1, args.warmup))
+    assert res["n_after"] == k_keep
+    t_full, _ = timed({}, max(2, args.steps // 4), 1)
+    paper_A = lambda n: SS.block_cost(n, d, m)       # App. A: A(n) = 4 n d^2 + 2 n^2 d + 2 n d m
     flops_full = L * block_flops(N)
     flops_dash = start_block * block_flops(N) + (L - start_block) * block_flops(k_keep)
     print(json.dumps({
@@ -173,13 +187,68 @@ def run_single_shot_bench(args, cfg):
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": "qwen_32k_single_shot", "N": N, "blocks": L, "start_block": start_block,
                    "reduction_ratio": rho, "protected": [first, last], "n_kept": k_keep, "hidden": d, "ffn": m,
-                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": dh, "rope_theta": 1.0e6},
+                   "q_heads": Hq, "kv_heads": Hkv, "head_dim": dh, "rope_theta": QWEN_BLOCKS["rope_theta"]},
         "full_model_ms": 1e3 * t_full, "speedup_vs_full_model": t_full / t_dash,
         "speedup_of_executed_flops": flops_full / flops_dash,
         "speedup_paper_formula": L * paper_A(N) / (start_block * paper_A(N) + (L - start_block) * paper_A(k_keep)),
         "roofline": {"bound": "mfma", "achieved": flops_dash / t_dash / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": flops_dash / t_dash / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
         "full_model_tflops": flops_full / t_full / 1e12}))
+
+
+def run_schedule_sweep_bench(args, cfg, workload):
+    """Two sweeps over halting schedules of the 28-block model, every schedule timed end to end beside the full
+    model:
+      qwen_32k_multi_shot   1-, 2-, 3- and 4-shot schedules under the same App. A budget as the single shot
+                            (same per-shot ratio, smallest one on a 1e-4 grid whose cost does not exceed it)
+      qwen_vl_8k_extreme    one shot at the reduction ratios of the paper's vision-language table (75 % ... 99 %) on
+                            an 8192-token prompt (Qwen2-VL-7B has the shapes of Qwen2.5-7B): short surviving
+                            sequences, where launch gaps and occupancy, not the matrix pipe, set the time
+    A step = one prefill under the first schedule of the sweep; `value` is its prompt tokens/s."""
+    from paper_2604_18103_amd import single_shot as SS
+
+    L, m, start_block, first, last = (QWEN_BLOCKS[k] for k in ("L", "m", "start_block", "first", "last"))
+    N, d = cfg.N, cfg.d
+    l0 = start_block - 1                      # index of the block after which the first decision is taken
+    if workload == "qwen_32k_multi_shot":
+        single = sum(SS.block_cost(t, d, m) for t in SS.schedule_lengths(N, L, {l0: 0.667}, first, last))
+        plans = []
+        for layers in ([l0], [l0, 18], [l0, 15, 21], [l0, 14, 18, 22]):
+            c = SS.comparable_multi_shot_ratio(N, L, layers, single, d, m, first, last)
+            plans.append((f"{len(layers)}-shot", layers, c))
+    else:
+        plans = [(f"{100 * c:.2f} % halted", [l0], c) for c in (0.75, 0.8889, 0.9375, 0.96, 0.99)]
+    timed, block_flops = _blocks_setup(cfg)
+    t_full, _ = timed({}, max(2, args.steps // 2), 1)
+    rows = []
+    for name, layers, c in plans:
+        lengths = SS.schedule_lengths(N, L, {l: c for l in layers}, first, last)
+        shots = {l: lengths[l + 1] for l in layers}
+        t, res = timed(shots, args.steps, max(1, args.warmup))
+        assert res["n_after"] == lengths[-1]
+        flops = sum(block_flops(t_) for t_ in lengths)
+        rows.append({"schedule": name, "decision_after_blocks": [l + 1 for l in layers], "ratio_per_shot": c,
+                     "rows_per_block": sorted(set(lengths), reverse=True), "ms": 1e3 * t,
+                     "speedup_vs_full_model": t_full / t,
+                     "speedup_of_executed_flops": L * block_flops(N) / flops,
+                     "speedup_paper_formula": L * SS.block_cost(N, d, m) / sum(SS.block_cost(t_, d, m) for t_ in lengths),
+                     "tflops": flops / t / 1e12,
+                     "ms_per_block_after_last_decision": 1e3 * (t - t_full * (layers[-1] + 1) / L) / (L - layers[-1] - 1)
+                     if len(layers) == 1 else None})
+    t0 = rows[0]["ms"] * 1e-3
+    print(json.dumps({
+        "metric": "prompt tokens/s of a 28-block prefill under the first schedule of the sweep "
+                  f"({rows[0]['schedule']}), Qwen2.5-7B shapes, N={N}",
+        "value": N / t0, "unit": "prompt tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * t0, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": workload, "N": N, "blocks": L, "protected": [first, last], "hidden": d, "ffn": m,
+                   "q_heads": cfg.n_q_heads, "kv_heads": cfg.n_kv_heads, "head_dim": cfg.head_dim,
+                   "rope_theta": QWEN_BLOCKS["rope_theta"]},
+        "full_model_ms": 1e3 * t_full, "full_model_tflops": L * block_flops(N) / t_full / 1e12,
+        "roofline": {"bound": "mfma", "achieved": rows[0]["tflops"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": rows[0]["tflops"] / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "schedules": rows}))
 
 
 def main():
@@ -189,7 +258,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="qwen_32k_half",
                     help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads; qwen_32k_chain is "
-                         "the 8-layer chain), or qwen_32k_single_shot (28 full blocks, one halting decision)")
+                         "the 8-layer chain), qwen_32k_single_shot (28 full blocks, one halting decision), "
+                         "qwen_32k_multi_shot (1- to 4-shot schedules under one budget) or qwen_vl_8k_extreme "
+                         "(one shot, 75 % to 99 % of the tokens halted)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run device-to-device copies of this many MiB (a plain copy kernel of known "
@@ -211,6 +282,12 @@ def main():
     B.lib()  # fail loudly if the HIP library is missing
     if args.workload == "qwen_32k_single_shot":
         run_single_shot_bench(args, I.CONFIGS["qwen_32k_chain"])
+        return
+    if args.workload == "qwen_32k_multi_shot":
+        run_schedule_sweep_bench(args, I.CONFIGS["qwen_32k_chain"], args.workload)
+        return
+    if args.workload == "qwen_vl_8k_extreme":
+        run_schedule_sweep_bench(args, I.scaled(I.CONFIGS["qwen_32k_chain"], 8192, N=8192), args.workload)
         return
     cfg = I.CONFIGS[args.workload]
     if args.workload == "qwen_32k_chain":

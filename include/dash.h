@@ -125,7 +125,10 @@ dash_status dash_flash_fwd(const dash_layer_params *params, const void *q, const
 /* Stage 1. delta = o @ w_o; x_next = x + delta (Sec. 3.1, Alg. 1 step 6); per-row partial sums of
  * delta^2 and x^2 taken from the fp32 accumulators: norm_partials [P, n, 2] fp32 (P-major) with
  * P = dash_norm_partials_per_row(params). delta_dbg NULL or fp32 [n,d].
- * workspace: device scratch of dash_workspace_bytes(params, n) (only part is used). */
+ * workspace: optional device scratch (NULL or 16-byte aligned). With few active rows the product has few
+ * output tiles; given scratch it is then cut along the contraction into parts that run side by side and
+ * are summed in a fixed order (as many parts as the scratch holds fp32 [n,d] sums; dash_workspace_bytes
+ * reserves enough for dash_attn_layer). Results do not depend on other calls, only on n and the scratch size. */
 dash_status dash_wo_residual_rownorm(const dash_layer_params *params, const void *o, const void *w_o,
                                      const void *x, int32_t n, void *x_next, float *norm_partials,
                                      float *delta_dbg, void *workspace, size_t workspace_bytes,
@@ -166,10 +169,14 @@ dash_status dash_decide_topk(const dash_layer_params *params, const float *score
 
 /* Front end of a layer in a chain (Eq. 1's LN and the q/k/v projections, which sit before the path):
  * h = x / sqrt(mean(x^2) + 1e-6) (unit gain); q = h @ w_q [d, Hq*dh]; k = h @ w_k; v = h @ w_v
- * [d, Hkv*dh]. bf16 only. h_scratch: device [n,d] bf16. */
+ * [d, Hkv*dh]. bf16 only. h_scratch: device [n,d] bf16.
+ * workspace: optional device scratch (NULL or 16-byte aligned) of dash_qkv_workspace_bytes(params, n_capacity)
+ * bytes, which lets the projections of a short active sequence split along the contraction (see
+ * dash_wo_residual_rownorm). */
+size_t dash_qkv_workspace_bytes(const dash_layer_params *params, int32_t n_capacity);
 dash_status dash_rmsnorm_qkv(const dash_layer_params *params, const void *x, const void *w_q,
                              const void *w_k, const void *w_v, int32_t n, void *q, void *k, void *v,
-                             void *h_scratch, void *hip_stream);
+                             void *h_scratch, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Rotary position embedding of the backbone (Qwen2.5 / Llama-3, Sec. 4.1) applied in place to q [n,Hq,dh] and
  * k [n,Hkv,dh] (bf16, device), with each row's ORIGINAL position active_idx[t]: the compacted active sequence
@@ -188,7 +195,7 @@ dash_status dash_rope_qk(const dash_layer_params *params, void *q, void *k, cons
  * 32c..32c+31 of W_gate, columns 64c+32..64c+63 the same columns of W_up (so that one GEMM tile holds gate and
  * up of the same features and the gating happens in its epilogue).
  * workspace: device, 256-byte aligned, >= dash_ffn_workspace_bytes(params, n, m) (the normalised rows, the
- * gated activations [n,m], row-norm partials). */
+ * gated activations [n,m], row-norm partials, split sums of the two products when n is small). */
 size_t dash_ffn_workspace_bytes(const dash_layer_params *params, int32_t n_capacity, int32_t m);
 dash_status dash_ffn_swiglu(const dash_layer_params *params, const void *x, const void *w_gate_up,
                             const void *w_down, int32_t n, int32_t m, void *x_out, void *workspace,

@@ -71,7 +71,9 @@ def lib() -> C.CDLL:
     L.dash_score_decide.argtypes = [pp, _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.dash_compact.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.dash_score_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
-    L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp]
+    L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.dash_qkv_workspace_bytes.restype = C.c_size_t
+    L.dash_qkv_workspace_bytes.argtypes = [pp, C.c_int32]
     L.dash_rope_qk.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_double, _vp]
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_score_diff_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
@@ -268,9 +270,14 @@ def dash_rope_qk(params, q, k, active_idx, n, theta_base) -> None:
            "dash_rope_qk")
 
 
-def dash_rmsnorm_qkv(params, x, w_q, w_k, w_v, n, q, k, v, h_scratch) -> None:
+def qkv_workspace_bytes(params, n_capacity: int) -> int:
+    return int(lib().dash_qkv_workspace_bytes(C.byref(params), int(n_capacity)))
+
+
+def dash_rmsnorm_qkv(params, x, w_q, w_k, w_v, n, q, k, v, h_scratch, workspace=None) -> None:
+    ws_n = workspace.numel() if workspace is not None else 0
     _check(lib().dash_rmsnorm_qkv(C.byref(params), _p(x), _p(w_q), _p(w_k), _p(w_v), int(n), _p(q), _p(k),
-                                  _p(v), _p(h_scratch), _stream()), "dash_rmsnorm_qkv")
+                                  _p(v), _p(h_scratch), _p(workspace), ws_n, _stream()), "dash_rmsnorm_qkv")
 
 
 def dash_validate_active_idx(active_idx, n, N, violations) -> None:

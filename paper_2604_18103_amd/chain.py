@@ -25,6 +25,7 @@ class ChainState:
     k: torch.Tensor
     v: torch.Tensor
     h: torch.Tensor
+    qkv_ws: torch.Tensor
     per_layer: list = field(default_factory=list)
 
 
@@ -37,7 +38,8 @@ def alloc_chain(d, n_q_heads, n_kv_heads, head_dim, n_capacity, device="cuda") -
         q=torch.empty((n_capacity, n_q_heads, head_dim), dtype=bf, device=device),
         k=torch.empty((n_capacity, n_kv_heads, head_dim), dtype=bf, device=device),
         v=torch.empty((n_capacity, n_kv_heads, head_dim), dtype=bf, device=device),
-        h=torch.empty((n_capacity, d), dtype=bf, device=device))
+        h=torch.empty((n_capacity, d), dtype=bf, device=device),
+        qkv_ws=torch.empty((max(B.qkv_workspace_bytes(p, n_capacity), 256),), dtype=torch.uint8, device=device))
 
 
 def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0: int, weights: list,
@@ -55,7 +57,7 @@ def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0
         if time_layers:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, state.q, state.k, state.v, state.h)
+        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, state.q, state.k, state.v, state.h, state.qkv_ws)
         if rope_theta is not None:
             B.dash_rope_qk(p, state.q, state.k, idx, n, rope_theta)
         B.dash_attn_layer(p, x, state.q, state.k, state.v, W["w_o"], idx, n, buf)

@@ -34,7 +34,7 @@ dash_status check_params(const dash_layer_params* p) {
 }
 
 struct Workspace {
-    size_t o_off, partials_off, counts_off, decide_off, total;
+    size_t o_off, partials_off, counts_off, decide_off, split_off, split_bytes, total;
 };
 
 Workspace carve(const dash_layer_params& p, int64_t n) {
@@ -49,6 +49,9 @@ Workspace carve(const dash_layer_params& p, int64_t n) {
     off = align_up(off + n_chunks * sizeof(int32_t), 256);
     w.decide_off = off;
     off = align_up(off + decide_workspace_bytes() + n_chunks * sizeof(int32_t), 256);
+    w.split_off = off;
+    w.split_bytes = wo_splitk_bytes(p, (int)n);  // split-K sums of the projection when few rows are active
+    off += w.split_bytes;
     w.total = off;
     return w;
 }
@@ -138,18 +141,17 @@ dash_status dash_wo_residual_rownorm(const dash_layer_params* p, const void* o, 
                                      const void* x, int32_t n, void* x_next, float* norm_partials,
                                      float* delta_dbg, void* workspace, size_t workspace_bytes,
                                      void* hip_stream) {
-    (void)workspace;
-    (void)workspace_bytes;
     dash_status st = check_params(p);
     if (st != DASH_OK) return st;
     if (n < 0) return DASH_ERR_INVALID_ARG;
     if (n == 0) return DASH_OK;
     if (!o || !w_o || !x || !x_next || !norm_partials) return DASH_ERR_INVALID_ARG;
     if (!aligned16(o) || !aligned16(w_o) || !aligned16(x) || !aligned16(x_next) ||
-        !aligned16(norm_partials) || !aligned16(delta_dbg))
+        !aligned16(norm_partials) || !aligned16(delta_dbg) || !aligned16(workspace))
         return DASH_ERR_INVALID_ARG;
-    return launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, norm_partials, delta_dbg,
-                                      (hipStream_t)hip_stream);
+    // the scratch is optional here: without it the product is never split along K
+    return launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, norm_partials, delta_dbg, workspace,
+                                      workspace ? workspace_bytes : 0, (hipStream_t)hip_stream);
 }
 
 dash_status dash_score_decide(const dash_layer_params* p, const float* norm_partials, int32_t n,
@@ -227,9 +229,14 @@ dash_status dash_score_rows(const float* delta, const void* x, int32_t n, int32_
     return launch_score_rows(delta, x, n, d, dtype, score_kind, scores, (hipStream_t)hip_stream);
 }
 
+size_t dash_qkv_workspace_bytes(const dash_layer_params* p, int32_t n_capacity) {
+    if (check_params(p) != DASH_OK || n_capacity < 0) return 0;
+    return qkv_workspace_bytes(*p, n_capacity);
+}
+
 dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const void* w_q, const void* w_k,
                              const void* w_v, int32_t n, void* q, void* k, void* v, void* h_scratch,
-                             void* hip_stream) {
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
     dash_status st = check_params(p);
     if (st != DASH_OK) return st;
     if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
@@ -238,9 +245,10 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const vo
     if (n == 0) return DASH_OK;
     if (!x || !w_q || !w_k || !w_v || !q || !k || !v || !h_scratch) return DASH_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(w_q) || !aligned16(w_k) || !aligned16(w_v) || !aligned16(q) ||
-        !aligned16(k) || !aligned16(v) || !aligned16(h_scratch))
+        !aligned16(k) || !aligned16(v) || !aligned16(h_scratch) || !aligned16(workspace))
         return DASH_ERR_INVALID_ARG;
-    return launch_rmsnorm_qkv(*p, x, w_q, w_k, w_v, n, q, k, v, h_scratch, (hipStream_t)hip_stream);
+    return launch_rmsnorm_qkv(*p, x, w_q, w_k, w_v, n, q, k, v, h_scratch, workspace,
+                              workspace ? workspace_bytes : 0, (hipStream_t)hip_stream);
 }
 
 size_t dash_ffn_workspace_bytes(const dash_layer_params* p, int32_t n_capacity, int32_t m) {
@@ -322,7 +330,7 @@ dash_status dash_attn_layer(const dash_layer_params* p, const void* x, const voi
     st = launch_flash_fwd(*p, q, k, v, active_idx, n, o, s);
     if (st != DASH_OK) return st;
     if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[1], s));
-    st = launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, partials, delta_dbg, s);
+    st = launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, partials, delta_dbg, ws + w.split_off, w.split_bytes, s);
     if (st != DASH_OK) return st;
     if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[2], s));
     st = launch_score_decide(*p, partials, norm_partials_per_row(p->d, p->dtype), n, scores, halt_mask,

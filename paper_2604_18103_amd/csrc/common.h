@@ -50,11 +50,15 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
                              const int32_t* active_idx, int n, void* o, hipStream_t s);
 // wo_gemm.hip
 int norm_partials_per_row(int d, int dtype);
+// split_ws / split_bytes: optional device scratch that lets products with few output tiles split along K
+size_t wo_splitk_bytes(const dash_layer_params& p, int n);
 dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o, const void* w_o,
                                        const void* x, int n, void* x_next, float* partials,
-                                       float* delta_dbg, hipStream_t s);
+                                       float* delta_dbg, void* split_ws, size_t split_bytes, hipStream_t s);
+size_t qkv_workspace_bytes(const dash_layer_params& p, int n);
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
-                               const void* w_v, int n, void* q, void* k, void* v, void* h, hipStream_t s);
+                               const void* w_v, int n, void* q, void* k, void* v, void* h, void* split_ws,
+                               size_t split_bytes, hipStream_t s);
 // score_decide.hip
 size_t decide_workspace_bytes();
 dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,

@@ -136,7 +136,9 @@ __device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(
 // 32c..32c+31, columns 64c+32..64c+63 = the up columns of the same features), so a wave's two 32-column
 // accumulator blocks are gate and up of the same 32 features and the epilogue writes silu(gate) * up,
 // N / 2 columns per row.
-enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1, EPI_SWIGLU = 2 };
+// EPI_SPLITK: the workgroup covers only the K steps of split blockIdx.y and writes its fp32 accumulators to
+// f32_out[split][M][N]; a reduction kernel adds the splits in order and applies one of the other epilogues.
+enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1, EPI_SWIGLU = 2, EPI_SPLITK = 3 };
 
 // MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
 // grid: when the 256-row tiles do not fill a whole number of rounds over the compute units, the tiles of
@@ -148,8 +150,9 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                                                                  int N, const __bf16* __restrict__ x,
                                                                  __bf16* __restrict__ out,  // x_next or C
                                                                  float* __restrict__ partials,
-                                                                 float* __restrict__ delta_dbg, int n_mtiles,
-                                                                 int first_tile) {
+                                                                 float* __restrict__ f32_out,  // delta (debug) or split sums
+                                                                 int n_mtiles, int first_tile,
+                                                                 int ksteps_per_split) {
     constexpr int BM = 64 * MB;   // rows of this workgroup's tile
     constexpr int WM = 32 * MB;   // rows of a wave's tile
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
@@ -171,6 +174,10 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    // K steps of this workgroup: all of them, or those of split blockIdx.y
+    const int ks0 = (int)blockIdx.y * ksteps_per_split;
+    const int n_ksteps = min(ksteps_per_split, K / kGK - ks0);
+
     // Staging. A tile: BM rows of 128 bytes, one load instruction = 8 rows; B tile: 64 rows of 512 bytes,
     // one instruction = 2 rows. Lane l lands in physical chunk l % (chunks per row) of its row and therefore
     // fetches the logical chunk that the swizzle maps there. Rows beyond M and columns beyond N are clamped:
@@ -182,13 +189,13 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     for (int i = 0; i < ADMA; ++i) {
         const int row = (wave * ADMA + i) * 8 + lane / 8;
         const int lchunk = (lane % 8) ^ ((row / 2) % 8);
-        a_ptr[i] = reinterpret_cast<const char*>(A + (size_t)min(m0 + row, M - 1) * K + lchunk * 8);
+        a_ptr[i] = reinterpret_cast<const char*>(A + (size_t)min(m0 + row, M - 1) * K + ks0 * kGK + lchunk * 8);
     }
 #pragma unroll
     for (int i = 0; i < BDMA; ++i) {
         const int row = (wave * BDMA + i) * 2 + lane / 32;
         const int lchunk = (lane % 32) ^ (4 * (row % 4));
-        b_ptr[i] = reinterpret_cast<const char*>(B + (size_t)row * N + min(n0 + lchunk * 8, N - 8));
+        b_ptr[i] = reinterpret_cast<const char*>(B + (size_t)(ks0 * kGK + row) * N + min(n0 + lchunk * 8, N - 8));
     }
     const size_t b_step = (size_t)kGK * N * sizeof(__bf16);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
@@ -209,72 +216,87 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     };
 
     const int tg = lane / 16, ti = lane % 16;
-    const int n_ksteps = K / kGK;
     // barrier that orders LDS traffic only
     auto lds_barrier = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     };
-    // 8 * MB MFMAs of one K step on the operand stage `st`
-    auto compute_step = [&](int st) {
+    // Fragments of one 16-wide slice: MB A fragments (16-byte reads) and two B fragments (transpose reads).
+    bf16x8 Af[2][MB], Bf[2][2];
+    auto read_frags = [&](int st, int ks, bf16x8* af, bf16x8* bfr) {
         const __bf16* sa = smem + st * kGStageElems;
         const __bf16* sb = sa + kGAElems;
 #pragma unroll
-        for (int ks = 0; ks < kGK / 16; ++ks) {
-            bf16x8 Af[MB], Bf[2];
-#pragma unroll
-            for (int a = 0; a < MB; ++a) {
-                const int row = wm * WM + 32 * a + j;
-                Af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((2 * ks + h) ^ ((row / 2) % 8)) * 8]);
-            }
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*64 + 32b + 16*(tg%2) + 4*(ti%4)
-                const int krow = 16 * ks + 8 * (tg / 2) + ti / 4;
-                const int col = wn * 64 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
-                const int scol = ((col / 8) ^ (4 * (krow % 4))) * 8 + col % 8;  // krow + 4 swizzles alike
-                const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
-                const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
-                Bf[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
-            }
-#pragma unroll
-            for (int a = 0; a < MB; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Af[a], Bf[b], acc[a][b], 0, 0, 0);
+        for (int a = 0; a < MB; ++a) {
+            const int row = wm * WM + 32 * a + j;
+            af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((2 * ks + h) ^ ((row / 2) % 8)) * 8]);
         }
-        // issue order: the fragment reads of the first 16-wide slice up front, then every MFMA paired with
-        // reads for the next slice, so that no MFMA waits for a read issued just before it
-        constexpr int RD = MB + 4, MF = 2 * MB;  // LDS reads and MFMAs per slice: 8 and 8, or 6 and 4
-        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
 #pragma unroll
-        for (int sl = 0; sl < 3; ++sl) {
-#pragma unroll
-            for (int i = 0; i < RD - MF; ++i) {  // half tiles: two reads behind each of the first two MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            }
-#pragma unroll
-            for (int i = 0; i < 2 * MF - RD; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
+        for (int b = 0; b < 2; ++b) {
+            // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*64 + 32b + 16*(tg%2) + 4*(ti%4)
+            const int krow = 16 * ks + 8 * (tg / 2) + ti / 4;
+            const int col = wn * 64 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
+            const int scol = ((col / 8) ^ (4 * (krow % 4))) * 8 + col % 8;  // krow + 4 swizzles alike
+            const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
+            const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
+            bfr[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, MF, 0);
     };
+    auto mfma_slice = [&](const bf16x8* af, const bf16x8* bfr) {
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+    };
+    // issue order of one slice: every MFMA paired with fragment reads of the slice after it
+    constexpr int RD = MB + 4, MF = 2 * MB;  // LDS reads and MFMAs per slice: 8 and 8, or 6 and 4
+    auto pin_slice = [] {
+#pragma unroll
+        for (int i = 0; i < RD - MF; ++i) {  // half tiles: two reads behind each of the first two MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2 * MF - RD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+    };
+    constexpr int kStepLoads = ADMA + BDMA;
     dma_next_step(0);
-    gemm_dma_wait();
-    __syncthreads();
-    // One round per K step: request the tiles of the next step into the other stage (last read in the
-    // previous round, which every wave left through the barrier), run this step's MFMAs, wait for the
-    // tiles, barrier.
-    for (int kt = 0; kt < n_ksteps; ++kt) {
-        if (kt + 1 < n_ksteps) dma_next_step((kt + 1) & 1);
-        compute_step(kt & 1);
+    if (n_ksteps > 1) {
+        dma_next_step(1);
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepLoads) : "memory");  // step 0 has landed, step 1 may be in flight
+    } else {
         gemm_dma_wait();
-        lds_barrier();
     }
+    __syncthreads();
+    read_frags(0, 0, Af[0], Bf[0]);
+    // One round per K step of four 16-wide slices. The fragments of a slice are read while the MFMAs of the
+    // slice before it run, across the step boundary too: the wait for the next step's tiles and the barrier
+    // that publishes them sit before the last slice's MFMAs, whose fragments are in registers by then, and
+    // the first slice of the next step is read from the other stage while those MFMAs run. After that
+    // barrier every wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it.
+    for (int kt = 0; kt < n_ksteps; ++kt) {
+        const int st = kt & 1;
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) {
+            read_frags(st, ks + 1, Af[(ks + 1) & 1], Bf[(ks + 1) & 1]);
+            mfma_slice(Af[ks & 1], Bf[ks & 1]);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) pin_slice();
+        gemm_dma_wait();
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the last slice's fragments are in registers
+        lds_barrier();
+        if (kt + 2 < n_ksteps) dma_next_step(st);
+        read_frags(st ^ 1, 0, Af[0], Bf[0]);  // after the last step: stale data, never used
+        mfma_slice(Af[1], Bf[1]);
+        pin_slice();
+    }
+    __syncthreads();  // the stale fragment reads of slower waves are harmless, but keep the epilogue's reuse simple
     // all waves are past the last barrier: the operand stages are free and are reused by the epilogue
 
     // Epilogue, per 32-row block of the wave's tile: stage the fp32 accumulators in LDS, then every lane
@@ -347,9 +369,9 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                         sx = fmaf(xf, xf, sx);
                     }
                     *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn_e) = ov;
-                    if (delta_dbg) {
-                        *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn_e) = d0;
-                        *reinterpret_cast<f32x4*>(delta_dbg + (size_t)gm * N + gn_e + 4) = d1;
+                    if (f32_out) {
+                        *reinterpret_cast<f32x4*>(f32_out + (size_t)gm * N + gn_e) = d0;
+                        *reinterpret_cast<f32x4*>(f32_out + (size_t)gm * N + gn_e + 4) = d1;
                     }
                 }
 #pragma unroll
@@ -361,6 +383,12 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                     const int p = tile_n * 4 + wn;
                     *reinterpret_cast<float2*>(partials + ((size_t)p * M + gm) * 2) = make_float2(sd, sx);
                 }
+            } else if (EPI == EPI_SPLITK) {
+                if (ok) {
+                    float* dst = f32_out + ((size_t)blockIdx.y * M + gm) * N + gn_e;
+                    *reinterpret_cast<f32x4*>(dst) = d0;
+                    *reinterpret_cast<f32x4*>(dst + 4) = d1;
+                }
             } else if (ok) {
                 bf16x8 ov;
 #pragma unroll
@@ -370,6 +398,93 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         }
         __syncthreads();
     }
+}
+
+// Second pass of a split-K product: adds the S split sums of sums[S][M][N] in the order s = 0..S-1 and applies
+// the epilogue EPI (same results layout as the one-pass kernel). A wave works on one row; a lane owns 8
+// consecutive columns, so the 8 lanes of a 64-column group hold that group's row sums for the norm partials.
+template <int EPI>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ sums, int S, int M, int N,
+                                                            const __bf16* __restrict__ x, __bf16* __restrict__ out,
+                                                            float* __restrict__ partials) {
+    const int lane = threadIdx.x % kWave;
+    const int wave_global = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) / kWave);
+    if (EPI == EPI_SWIGLU) {
+        // 4 lanes per 64-column group (32 gate + 32 up columns): 16 groups = 1024 input columns per wave
+        const int segs = (N + 1023) / 1024;
+        const int row = wave_global / segs, seg = wave_global % segs;
+        if (row >= M) return;
+        const int grp = seg * 16 + lane / 4, c = lane % 4;
+        const int gcol = grp * 64 + 8 * c;  // gate columns gcol..gcol+7, up columns gcol+32..
+        if (gcol >= N) return;
+        float g[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, u[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int sp = 0; sp < S; ++sp) {
+            const float* src = sums + ((size_t)sp * M + row) * N + gcol;
+            const f32x4 g0 = *reinterpret_cast<const f32x4*>(src), g1 = *reinterpret_cast<const f32x4*>(src + 4);
+            const f32x4 u0 = *reinterpret_cast<const f32x4*>(src + 32), u1 = *reinterpret_cast<const f32x4*>(src + 36);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                g[e] += g0[e];
+                g[4 + e] += g1[e];
+                u[e] += u0[e];
+                u[4 + e] += u1[e];
+            }
+        }
+        bf16x8 ov;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ov[e] = (__bf16)(g[e] / (1.0f + __expf(-g[e])) * u[e]);
+        *reinterpret_cast<bf16x8*>(out + (size_t)row * (N / 2) + grp * 32 + 8 * c) = ov;
+        return;
+    }
+    const int segs = (N + 511) / 512;  // 8 groups of 64 columns per wave
+    const int row = wave_global / segs, seg = wave_global % segs;
+    if (row >= M) return;
+    const int grp = seg * 8 + lane / 8;
+    const int col = grp * 64 + 8 * (lane % 8);
+    const bool ok = col < N;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (ok) {
+        for (int sp = 0; sp < S; ++sp) {
+            const float* src = sums + ((size_t)sp * M + row) * N + col;
+            const f32x4 a0 = *reinterpret_cast<const f32x4*>(src), a1 = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                acc[e] += a0[e];
+                acc[4 + e] += a1[e];
+            }
+        }
+    }
+    if (EPI == EPI_STORE) {
+        if (ok) {
+            bf16x8 ov;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ov[e] = (__bf16)acc[e];
+            *reinterpret_cast<bf16x8*>(out + (size_t)row * N + col) = ov;
+        }
+        return;
+    }
+    float sd = 0.f, sx = 0.f;
+    if (ok) {
+        const bf16x8 xr = *reinterpret_cast<const bf16x8*>(x + (size_t)row * N + col);
+        bf16x8 ov;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float xf = (float)xr[e];
+            ov[e] = (__bf16)(xf + acc[e]);
+            sd = fmaf(acc[e], acc[e], sd);
+            sx = fmaf(xf, xf, sx);
+        }
+        *reinterpret_cast<bf16x8*>(out + (size_t)row * N + col) = ov;
+    }
+#pragma unroll
+    for (int off = 4; off > 0; off >>= 1) {
+        sd += __shfl_xor(sd, off);
+        sx += __shfl_xor(sx, off);
+    }
+    // one partial pair per 64-column group, as the one-pass kernel writes them; groups beyond N (the rest of a
+    // 256-column tile) hold zeros
+    if (lane % 8 == 0 && grp < 4 * ((N + kGN - 1) / kGN))
+        *reinterpret_cast<float2*>(partials + ((size_t)grp * M + row) * 2) = make_float2(sd, sx);
 }
 
 // h = x / sqrt(mean(x^2) + 1e-6), unit gain; one wave per row.
@@ -414,40 +529,88 @@ static int compute_units() {
     return n;
 }
 
+// Split-K: a product with few output tiles and a long contraction (few active rows) leaves most compute units
+// idle and the few busy ones with a long serial loop. Such a product is cut along K into S parts that run side
+// by side, each writing fp32 sums to scratch, and a second kernel adds the parts in a fixed order and applies
+// the epilogue. Used when the tiles would occupy at most half of the units.
+constexpr int kSplitSizingUnits = 256;  // unit count assumed when sizing the scratch (the launch uses the real one)
+constexpr int kSplitMinSteps = 4;       // K steps per part at least
+
+static int splitk_parts(int tiles, int ksteps, int cu) {
+    if (cu <= 0 || 2 * tiles > cu) return 1;
+    const int s = min(cu / tiles, ksteps / kSplitMinSteps);
+    return s < 2 ? 1 : s;
+}
+
+// Scratch bytes that let every product of up to M_cap rows with this K and N split as far as it would like to.
+size_t gemm_splitk_bytes(int M_cap, int K, int N) {
+    const int nt = (N + kGN - 1) / kGN, ksteps = K / kGK;
+    size_t best = 0;
+    for (int mt = 1; mt <= (M_cap + kGM - 1) / kGM; ++mt) {
+        const int parts = splitk_parts(mt * nt, ksteps, kSplitSizingUnits);
+        if (parts < 2) break;  // more row tiles only split less
+        const size_t rows = (size_t)min(mt * kGM, M_cap);
+        best = max(best, (size_t)parts * rows * N * sizeof(float));
+    }
+    return (best + 255) / 256 * 256;
+}
+
 // 256x256 tiles for every whole round over the compute units; if the tiles left over would occupy at most
-// half of the units, they are run as 128-row half tiles by a second launch (same kernel, MB = 2).
+// half of the units, they are run as 128-row half tiles by a second launch (same kernel, MB = 2). Products with
+// few tiles are split along K when `split_ws` (device scratch of `split_bytes`) allows.
 template <int EPI>
 static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
-                               __bf16* out, float* partials, float* delta_dbg, hipStream_t s) {
+                               __bf16* out, float* partials, float* delta_dbg, void* split_ws, size_t split_bytes,
+                               hipStream_t s) {
     static const hipError_t attr4 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                                          (int)kGemmSmemBytes);
     static const hipError_t attr2 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 2>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                                          (int)kGemmSmemBytes);
-    if (attr4 != hipSuccess || attr2 != hipSuccess) return DASH_ERR_HIP;
+    static const hipError_t attr_s = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_SPLITK, 4>,
+                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                          (int)kGemmSmemBytes);
+    if (attr4 != hipSuccess || attr2 != hipSuccess || attr_s != hipSuccess) return DASH_ERR_HIP;
     const int mt = (M + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN, tiles = mt * nt;
-    const int cu = compute_units();
+    const int cu = compute_units(), ksteps = K / kGK;
+    if (split_ws && !delta_dbg) {
+        int parts = splitk_parts(tiles, ksteps, cu);
+        const size_t per_part = (size_t)M * N * sizeof(float);
+        if ((size_t)parts * per_part > split_bytes) parts = (int)(split_bytes / per_part);
+        if (parts >= 2) {
+            const int per = (ksteps + parts - 1) / parts;
+            parts = (ksteps + per - 1) / per;  // every part has at least one K step
+            float* sums = reinterpret_cast<float*>(split_ws);
+            hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(tiles, parts), dim3(kGThreads), kGemmSmemBytes, s,
+                               A, B, M, K, N, nullptr, nullptr, nullptr, sums, mt, 0, per);
+            const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
+            const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
+            hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((waves * kWave + 255) / 256)), dim3(256), 0,
+                               s, sums, parts, M, N, x, out, partials);
+            return launch_status();
+        }
+    }
     int rest = cu > 0 ? tiles % cu : 0;
     if (2 * rest > cu) rest = 0;
     const int full = tiles - rest;
     if (full > 0)
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
-                           out, partials, delta_dbg, mt, 0);
+                           out, partials, delta_dbg, mt, 0, ksteps);
     if (rest > 0)
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
-                           x, out, partials, delta_dbg, mt, full);
+                           x, out, partials, delta_dbg, mt, full, ksteps);
     return launch_status();
 }
 
-static dash_status launch_gemm_store(const __bf16* A, const __bf16* B, int M, int K, int N, __bf16* C,
-                                     hipStream_t s) {
-    return launch_gemm<EPI_STORE>(A, B, M, K, N, nullptr, C, nullptr, nullptr, s);
+size_t wo_splitk_bytes(const dash_layer_params& p, int n) {
+    if (p.dtype != DASH_BF16) return 0;
+    return gemm_splitk_bytes(n, p.n_q_heads * p.head_dim, p.d);
 }
 
 dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o, const void* w_o,
                                        const void* x, int n, void* x_next, float* partials,
-                                       float* delta_dbg, hipStream_t s) {
+                                       float* delta_dbg, void* split_ws, size_t split_bytes, hipStream_t s) {
     if (n == 0) return DASH_OK;
     const int K = p.n_q_heads * p.head_dim, N = p.d;
     if (p.dtype == DASH_F32) {
@@ -457,13 +620,15 @@ dash_status launch_wo_residual_rownorm(const dash_layer_params& p, const void* o
         return launch_status();
     }
     return launch_gemm<EPI_RESIDUAL_NORM>((const __bf16*)o, (const __bf16*)w_o, n, K, N, (const __bf16*)x,
-                                          (__bf16*)x_next, partials, delta_dbg, s);
+                                          (__bf16*)x_next, partials, delta_dbg, split_ws, split_bytes, s);
 }
 
+static size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+
 size_t ffn_workspace_bytes(const dash_layer_params& p, int n, int m) {
-    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-    return up((size_t)n * p.d * 2) + up((size_t)n * m * 2) +
-           up((size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float));
+    return up256((size_t)n * p.d * 2) + up256((size_t)n * m * 2) +
+           up256((size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float)) +
+           max(gemm_splitk_bytes(n, p.d, 2 * m), gemm_splitk_bytes(n, m, p.d));
 }
 
 // out = x + (silu(h W_gate) * (h W_up)) W_down with h = RMSNorm(x) (Alg. 1 step 7): row norm, one GEMM over
@@ -471,32 +636,43 @@ size_t ffn_workspace_bytes(const dash_layer_params& p, int n, int m) {
 dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const void* w_gate_up, const void* w_down,
                               int n, int m, void* x_out, void* ws, hipStream_t s) {
     if (n == 0) return DASH_OK;
-    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     char* base = reinterpret_cast<char*>(ws);
     __bf16* h = reinterpret_cast<__bf16*>(base);
-    __bf16* act = reinterpret_cast<__bf16*>(base + up((size_t)n * p.d * 2));
-    float* partials = reinterpret_cast<float*>(base + up((size_t)n * p.d * 2) + up((size_t)n * m * 2));
+    __bf16* act = reinterpret_cast<__bf16*>(base + up256((size_t)n * p.d * 2));
+    float* partials = reinterpret_cast<float*>(base + up256((size_t)n * p.d * 2) + up256((size_t)n * m * 2));
+    char* split_ws = reinterpret_cast<char*>(partials) +
+                     up256((size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float));
+    const size_t split_bytes = max(gemm_splitk_bytes(n, p.d, 2 * m), gemm_splitk_bytes(n, m, p.d));
     const int blocks = (int)(((size_t)n * kWave + 255) / 256);
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(blocks), dim3(256), 0, s, (const __bf16*)x, n, p.d, h);
     dash_status st = launch_gemm<EPI_SWIGLU>(h, (const __bf16*)w_gate_up, n, p.d, 2 * m, nullptr, act, nullptr,
-                                             nullptr, s);
+                                             nullptr, split_ws, split_bytes, s);
     if (st != DASH_OK) return st;
     return launch_gemm<EPI_RESIDUAL_NORM>(act, (const __bf16*)w_down, n, m, p.d, (const __bf16*)x,
-                                          (__bf16*)x_out, partials, nullptr, s);
+                                          (__bf16*)x_out, partials, nullptr, split_ws, split_bytes, s);
+}
+
+size_t qkv_workspace_bytes(const dash_layer_params& p, int n) {
+    if (p.dtype != DASH_BF16) return 0;
+    return gemm_splitk_bytes(n, p.d, p.n_q_heads * p.head_dim);  // the widest of the three projections
 }
 
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
-                               const void* w_v, int n, void* q, void* k, void* v, void* hbuf,
-                               hipStream_t s) {
+                               const void* w_v, int n, void* q, void* k, void* v, void* hbuf, void* split_ws,
+                               size_t split_bytes, hipStream_t s) {
     if (n == 0) return DASH_OK;
     const int d = p.d, Dq = p.n_q_heads * p.head_dim, Dkv = p.n_kv_heads * p.head_dim;
     const int blocks = (int)(((size_t)n * kWave + 255) / 256);
     hipLaunchKernelGGL(rmsnorm_kernel, dim3(blocks), dim3(256), 0, s, (const __bf16*)x, n, d, (__bf16*)hbuf);
-    dash_status st = launch_gemm_store((const __bf16*)hbuf, (const __bf16*)w_q, n, d, Dq, (__bf16*)q, s);
+    const __bf16* h = (const __bf16*)hbuf;
+    dash_status st = launch_gemm<EPI_STORE>(h, (const __bf16*)w_q, n, d, Dq, nullptr, (__bf16*)q, nullptr, nullptr,
+                                            split_ws, split_bytes, s);
     if (st != DASH_OK) return st;
-    st = launch_gemm_store((const __bf16*)hbuf, (const __bf16*)w_k, n, d, Dkv, (__bf16*)k, s);
+    st = launch_gemm<EPI_STORE>(h, (const __bf16*)w_k, n, d, Dkv, nullptr, (__bf16*)k, nullptr, nullptr, split_ws,
+                                split_bytes, s);
     if (st != DASH_OK) return st;
-    return launch_gemm_store((const __bf16*)hbuf, (const __bf16*)w_v, n, d, Dkv, (__bf16*)v, s);
+    return launch_gemm<EPI_STORE>(h, (const __bf16*)w_v, n, d, Dkv, nullptr, (__bf16*)v, nullptr, nullptr, split_ws,
+                                  split_bytes, s);
 }
 
 }  // namespace dash

@@ -1,4 +1,5 @@
-"""Driver of the single-shot schedule (Alg. 1): L full blocks, one halting decision at the start layer l_s.
+"""Driver of the halting schedules over L full blocks: the single-shot schedule of Alg. 1 (one decision at the
+start layer l_s) and multi-shot schedules (decisions at several blocks, App. D).
 
 Every step of a block runs in the HIP library:
     q, k, v      = RMSNorm(H) W_q, W_k, W_v ; RoPE at the original positions        dash_rmsnorm_qkv, dash_rope_qk
@@ -9,7 +10,7 @@ At l = l_s the layer call also scores the rows (Eq. 2) and picks S* = TopK (Eq. 
 on all rows (Alg. 1 step 7 comes before the selection takes effect); then the rows that halt are written to the
 full-length result at their original positions (they keep their last updated state, Sec. 3.4) and the kept rows
 are gathered for the blocks l > l_s. The survivors are written to the result after the last block. One 4-byte
-read-back, at l_s, sizes the later launches.
+read-back per decision sizes the later launches.
 """
 from __future__ import annotations
 
@@ -35,6 +36,7 @@ class BlockState:
     x_a: torch.Tensor
     x_b: torch.Tensor
     ffn_ws: torch.Tensor
+    qkv_ws: torch.Tensor
 
 
 def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda") -> BlockState:
@@ -52,39 +54,46 @@ def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda
         chunk_counts=torch.empty(((cap + 63) // 64,), dtype=torch.int32, device=device),
         x_a=torch.empty((cap, d), dtype=bf, device=device),
         x_b=torch.empty((cap, d), dtype=bf, device=device),
-        ffn_ws=torch.empty((max(B.ffn_workspace_bytes(p, cap, m), 256),), dtype=torch.uint8, device=device))
+        ffn_ws=torch.empty((max(B.ffn_workspace_bytes(p, cap, m), 256),), dtype=torch.uint8, device=device),
+        qkv_ws=torch.empty((max(B.qkv_workspace_bytes(p, cap), 256),), dtype=torch.uint8, device=device))
 
 
-def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | None, k_keep: int,
-                    rope_theta=None, final: torch.Tensor | None = None, on_block=None) -> dict:
+def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, rope_theta=None,
+                 final: torch.Tensor | None = None, on_block=None) -> dict:
     """Run len(weights) blocks on x0 [N, d] (all N tokens active at the start). weights[l] = dict(w_q, w_k, w_v,
-    w_o, w_gate_up, w_down) of device tensors. l_s = None runs the full model (no halting). k_keep = tokens kept
-    after block l_s. `final` [N, d] receives every token's last state. `on_block(l, x_in, idx, n, st, x_out)` is
-    called after every block (after a device synchronisation) for checks. Returns {n_after, final}."""
+    w_o, w_gate_up, w_down) of device tensors. `shots` maps a block index to the number of rows kept after that
+    block: one entry is the single-shot schedule of Alg. 1, several entries are a multi-shot schedule (every
+    decision ranks the rows still active by their Delta_attn in that block), none is the full model. `final`
+    [N, d] receives every token's last state. `on_block(l, x_in, idx, n, st, x_out)` is called after every block
+    (after a device synchronisation) for checks. One 4-byte read-back per decision sizes the later launches.
+    Returns {n_after, final, idx}."""
     p, buf = st.params, st.buf
     N, d = x0.shape
     if final is None:
         final = torch.empty_like(x0)
     idx = torch.arange(N, dtype=torch.int32, device=x0.device)
+    idx_spare = [torch.empty_like(idx), torch.empty_like(idx)]
+    n_shot = 0
     x, n = x0, N
     spare = [st.x_a, st.x_b]
     for l, W in enumerate(weights):
         x_out = spare[l & 1]
-        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, st.q, st.k, st.v, st.h)
+        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, st.q, st.k, st.v, st.h, st.qkv_ws)
         if rope_theta is not None:
             B.dash_rope_qk(p, st.q, st.k, idx, n, rope_theta)
-        if l_s is not None and l == l_s:
-            p.rule, p.k_keep = B.RULE_TOPK, int(k_keep)
+        if l in shots:
+            p.rule, p.k_keep = B.RULE_TOPK, int(shots[l])
             B.dash_attn_layer(p, x, st.q, st.k, st.v, W["w_o"], idx, n, buf)     # H~ in buf.x_next, mask, S*
             p.rule = B.RULE_NONE
             B.dash_ffn_swiglu(p, buf.x_next, W["w_gate_up"], W["w_down"], n, st.m, buf.x_next, st.ffn_ws)
             # the rows that halt now keep this state; the kept rows go on (gathered from the finished block)
             B.dash_scatter_rows(buf.x_next, idx, buf.halt_mask, 1, n, d, p.dtype, N, final)
             old_idx = idx
-            idx = torch.empty_like(buf.new_active_idx)
+            idx = idx_spare[n_shot & 1]
+            n_shot += 1
             B.dash_compact(p, buf.halt_mask, None, old_idx, buf.x_next, n, x_out, idx, buf.n_active_out,
                            buf.workspace)
-            n_new = int(buf.n_active_out.item())          # the one host read of the schedule
+            n_new = int(buf.n_active_out.item())          # the one host read of this decision
             if on_block is not None:
                 on_block(l, x, old_idx, n, st, buf.x_next)
             x, n = x_out, n_new
@@ -98,3 +107,45 @@ def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | 
             x = x_out
     B.dash_scatter_rows(x, idx, None, 0, n, d, p.dtype, N, final)
     return {"n_after": n, "final": final, "idx": idx}
+
+
+def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | None, k_keep: int,
+                    rope_theta=None, final: torch.Tensor | None = None, on_block=None) -> dict:
+    """Alg. 1: one decision after block l_s keeping k_keep rows; l_s = None runs the full model."""
+    shots = {} if l_s is None else {int(l_s): int(k_keep)}
+    return run_schedule(st, x0, weights, shots, rope_theta=rope_theta, final=final, on_block=on_block)
+
+
+def block_cost(n, d, m) -> float:
+    """Per-block prefill FLOPs proxy A(n) = 4 n d^2 + 2 n^2 d + 2 n d m of App. A."""
+    n, d, m = float(n), float(d), float(m)
+    return 4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m
+
+
+def schedule_lengths(n, L, ratios: dict, n_first=0, n_last=0) -> list:
+    """Rows each of L blocks runs on when block l applies compression ratio ratios[l] to the rows that enter it
+    (kept count by App. A's rule on the current length; the deciding block itself still runs on all of them)."""
+    out, cur = [], int(n)
+    for l in range(int(L)):
+        out.append(cur)
+        if l in ratios:
+            cur = B.keep_count(cur, ratios[l], n_first, n_last, paper_impl_rounding=True)
+    return out
+
+
+def comparable_multi_shot_ratio(n, L, shot_layers, target_cost, d, m, n_first=0, n_last=0, grid=10000) -> float:
+    """Common per-shot compression ratio (a multiple of 1 / grid) of a multi-shot schedule whose App. A cost does
+    not exceed target_cost: the smallest such ratio, found by bisection (the cost falls as the ratio grows)."""
+    def cost(i):
+        c = i / grid
+        return sum(block_cost(t, d, m) for t in schedule_lengths(n, L, {l: c for l in shot_layers}, n_first, n_last))
+    lo, hi = 0, grid
+    if cost(hi) > target_cost:
+        raise ValueError("no ratio on the grid meets the budget")
+    while lo < hi:
+        mid = (lo + hi) // 2
+        if cost(mid) <= target_cost:
+            hi = mid
+        else:
+            lo = mid + 1
+    return lo / grid

@@ -51,3 +51,23 @@ def test_host_helpers_validate_params():
     bad = B.make_params(3584, 28, 5, 128)
     assert B.workspace_bytes(bad, 100) == 0 and B.layer_flops(bad, 100) == 0.0
     assert B.lib().dash_status_string(-3).decode().startswith("workspace")
+
+
+def test_schedule_host_helpers_agree_with_the_oracle():
+    """Host arithmetic of the schedule driver (block lengths, App. A cost, comparable multi-shot ratio: bisection)
+    against the oracle's own versions (plain scan)."""
+    from oracle import reference as ref
+    from paper_2604_18103_amd import single_shot as SS
+    d, m, L = 3584, 18944, 28
+    for n in (8192, 32768):
+        assert SS.block_cost(n, d, m) == ref.flops_A(n, d, m)
+        one = {11: 0.667}
+        assert SS.schedule_lengths(n, L, one, 64, 32) == ref.schedule_lengths(n, L, one, 64, 32)
+        target = ref.schedule_flops(ref.schedule_lengths(n, L, one, 64, 32), d, m)
+        for layers in ([11], [11, 19], [11, 16, 22], [11, 15, 19, 23]):
+            c = SS.comparable_multi_shot_ratio(n, L, layers, target, d, m, 64, 32)
+            assert c == ref.comparable_multi_shot_ratio(n, L, layers, target, d, m, 64, 32)
+            shots = {l: c for l in layers}
+            assert SS.schedule_lengths(n, L, shots, 64, 32) == ref.schedule_lengths(n, L, shots, 64, 32)
+    with pytest.raises(ValueError):
+        SS.comparable_multi_shot_ratio(1000, 4, [1], 0.0, 64, 128)

@@ -47,6 +47,76 @@ def test_ffn_swiglu_matches_oracle(shape):
     assert torch.equal(gx, out)
 
 
+# ---------------------------------------------------------------- few active rows: products split along K
+
+@pytest.mark.parametrize("shape", [(177, 56, 64, 3584), (64, 9, 64, 256), (300, 8, 128, 512), (1, 16, 64, 128)],
+                         ids=lambda t: "n%d_hq%d_dh%d_d%d" % t)
+def test_projection_split_along_k_matches_oracle_and_one_pass(shape):
+    """With scratch the output projection of a short active sequence is cut along the contraction (here 14, 2,
+    4 and 4 parts, the last part shorter where K steps do not divide evenly): x_next and the row sums of squares
+    against the oracle, and against the one-pass product of the same library (no scratch)."""
+    n, hq, dh, d = shape
+    K = hq * dh
+    rng = np.random.default_rng(200 + n)
+    o = I.round_to_bf16(rng.standard_normal((n, K)))
+    w = I.round_to_bf16(rng.standard_normal((K, d)) / np.sqrt(K))
+    x = I.round_to_bf16(rng.standard_normal((n, d)) * np.exp(0.5 * rng.standard_normal((n, 1))))
+    p = B.make_params(d, hq, hq, dh)
+    P_ = B.norm_partials_per_row(p)
+    ws = torch.empty((B.workspace_bytes(p, n),), dtype=torch.uint8, device="cuda")
+    assert ws.numel() >= 2 * n * d * 4                   # room for at least two parts
+    delta = ref.project(o, w)
+    want = ref.residual(x, delta)
+    got = {}
+    for name, scratch in (("split", ws), ("one_pass", None)):
+        xn = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+        parts = torch.full((P_, n, 2), float("nan"), dtype=torch.float32, device="cuda")
+        B.dash_wo_residual_rownorm(p, _dev(o), _dev(w), _dev(x), n, xn, parts, None, scratch)
+        torch.cuda.synchronize()
+        sums = parts.double().sum(dim=0).cpu().numpy()   # every partial slot written (no NaN left)
+        assert P.row_rel_err(_f(xn), want).max() <= P.X_TOL["bf16"]
+        np.testing.assert_allclose(sums[:, 0], (delta ** 2).sum(axis=1), rtol=1e-4)
+        np.testing.assert_allclose(sums[:, 1], (x ** 2).sum(axis=1), rtol=1e-5)
+        got[name] = (_f(xn), sums)
+    # the two differ only in the order of fp32 additions: at most one bf16 step of the result, plus the fp32
+    # difference itself where x and delta cancel
+    a, b = got["split"][0], got["one_pass"][0]
+    assert np.all(np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 1e-4 * (np.abs(x) + np.abs(delta)))
+    np.testing.assert_allclose(got["split"][1], got["one_pass"][1], rtol=1e-5)
+
+
+@pytest.mark.parametrize("shape", [(150, 512, 576), (40, 1024, 2048)], ids=lambda t: "n%d_d%d_m%d" % t)
+def test_ffn_and_front_end_with_few_rows_split_along_k(shape):
+    """Short sequences through the feed-forward (both products split: K = d and K = m, m / 64 odd in the first
+    case) and the q/k/v projections with scratch, against the oracle."""
+    n, d, m = shape
+    cfg = I.LayerConfig("ffn_small", "bf16", n, n, d, 8, 2, 64, 0.3, seed=300 + n)
+    x = I.make_hidden(cfg)
+    W = I.make_ffn_weights(cfg, 0, m)
+    p = P.params_for(cfg)
+    out = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty((B.ffn_workspace_bytes(p, n, m),), dtype=torch.uint8, device="cuda")
+    B.dash_ffn_swiglu(p, _dev(x), B.interleave_gate_up(_dev(W["w_gate"]), _dev(W["w_up"])), _dev(W["w_down"]), n, m,
+                      out, ws)
+    torch.cuda.synchronize()
+    want = ref.ffn_swiglu(x, W["w_gate"], W["w_up"], W["w_down"])
+    assert P.row_rel_err(_f(out), want).max() <= P.X_TOL["bf16"]
+    upd_err = np.abs((_f(out) - x) - (want - x)).max(axis=1) / np.maximum(np.abs(want).max(axis=1), 1e-30)
+    assert upd_err.max() <= P.X_TOL["bf16"]
+    Wp = I.make_projection_weights(cfg, 0)
+    q = torch.empty((n, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    k = torch.empty((n, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty_like(k)
+    h = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    qws = torch.empty((B.qkv_workspace_bytes(p, n),), dtype=torch.uint8, device="cuda")
+    assert qws.numel() >= 2 * n * cfg.n_q_heads * cfg.head_dim * 4
+    B.dash_rmsnorm_qkv(p, _dev(x), _dev(Wp["w_q"]), _dev(Wp["w_k"]), _dev(Wp["w_v"]), n, q, k, v, h, qws)
+    torch.cuda.synchronize()
+    oq, ok, ov = ref.rmsnorm_qkv(x, Wp["w_q"], Wp["w_k"], Wp["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim)
+    for got, want_ in ((q, oq), (k, ok), (v, ov)):
+        assert P.row_rel_err(_f(got).reshape(n, -1), want_.reshape(n, -1)).max() <= 2e-2
+
+
 def test_scatter_rows_matches_oracle():
     n, d, N = 333, 256, 1000
     rng = np.random.default_rng(60)
@@ -130,6 +200,73 @@ def test_single_shot_schedule_teacher_forced_against_oracle():
     np.testing.assert_array_equal(final[surv], _f(last[:k_keep]))
     assert not np.array_equal(final[surv], seen["state"][halt == 0])                # they did move on
     print("single shot: kept", k_keep, "of", N, "band rows", seen["band"])
+
+
+def test_multi_shot_schedule_teacher_forced_against_oracle():
+    """Decisions after blocks 1 and 3 of five (App. D's multi-shot variant; protected ranks in the current active
+    order): every block against the oracle on the block's actual GPU input, each decision against the oracle's
+    TopK on the rows still active, and the full-length result: a token holds the state of the block at whose
+    end it stopped."""
+    N, d, m, L, theta = 650, 256, 512, 5, 1.0e6
+    first, last = 16, 8
+    cfg = I.LayerConfig("blocks_ms", "bf16", N, N, d, 4, 2, 64, 0.4, seed=72)
+    Wnp = []
+    for l in range(L):
+        w = I.make_projection_weights(cfg, l)
+        w.update(I.make_ffn_weights(cfg, l, m))
+        Wnp.append(w)
+    Wdev = []
+    for w in Wnp:
+        dw = {k: _dev(w[k]) for k in ("w_q", "w_k", "w_v", "w_o", "w_down")}
+        dw["w_gate_up"] = B.interleave_gate_up(_dev(w["w_gate"]), _dev(w["w_up"]))
+        Wdev.append(dw)
+    st = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
+    st.params.keep_first_n, st.params.keep_last_n = first, last
+    lengths = SS.schedule_lengths(N, L, {1: 0.4, 3: 0.5}, first, last)
+    assert lengths == ref.schedule_lengths(N, L, {1: 0.4, 3: 0.5}, first, last)
+    shots = {1: lengths[2], 3: lengths[4]}
+    assert N > shots[1] > shots[3] > first + last
+    seen = {"n_in": [], "stopped": {}, "active": np.arange(N)}
+
+    def check(l, x_in, idx, n, st_, x_out):
+        xs, idx_np = _f(x_in[:n]), idx[:n].cpu().numpy()
+        np.testing.assert_array_equal(idx_np, seen["active"])
+        seen["n_in"].append(n)
+        W = Wnp[l]
+        oq, ok, ov = ref.rmsnorm_qkv(xs, W["w_q"], W["w_k"], W["w_v"], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                                     pos=idx_np, rope_theta=theta)
+        qs, ks, vs = _f(st_.q[:n]), _f(st_.k[:n]), _f(st_.v[:n])
+        assert P.row_rel_err(qs.reshape(n, -1), oq.reshape(n, -1)).max() <= 2e-2
+        assert P.row_rel_err(ks.reshape(n, -1), ok.reshape(n, -1)).max() <= 2e-2
+        k_keep = shots.get(l, n)
+        rule = ref.RULE_TOPK if l in shots else ref.RULE_NONE
+        o = ref.attn_layer(xs, qs, ks, vs, W["w_o"], idx_np, rule=rule, k_keep=k_keep, keep_first_n=first,
+                           keep_last_n=last)
+        h_next = ref.ffn_swiglu(o.x_next, W["w_gate"], W["w_up"], W["w_down"])
+        assert P.row_rel_err(_f(x_out[:n]), h_next).max() <= P.X_TOL["bf16"]
+        if l in shots:
+            halt = st_.buf.halt_mask[:n].cpu().numpy()
+            assert int((halt == 0).sum()) == k_keep == o.n_active_out
+            assert not halt[:first].any() and not halt[n - last:].any()       # ranks in the current order
+            thr = np.sort(o.scores[first:n - last])[::-1][k_keep - first - last - 1]
+            band = np.abs(o.scores - thr) <= P.BAND_REL * thr
+            assert np.array_equal(halt[~band], o.halt[~band])
+            state = _f(x_out[:n])
+            for r in np.nonzero(halt == 1)[0]:
+                seen["stopped"][int(idx_np[r])] = state[r].copy()
+            seen["active"] = idx_np[halt == 0]
+
+    res = SS.run_schedule(st, _dev(I.make_hidden(cfg)), Wdev, shots, rope_theta=theta, on_block=check)
+    torch.cuda.synchronize()
+    assert seen["n_in"] == lengths and res["n_after"] == shots[3]
+    final = _f(res["final"])
+    assert len(seen["stopped"]) == N - shots[3]
+    for pos, state in seen["stopped"].items():
+        np.testing.assert_array_equal(final[pos], state)
+    surv = res["idx"][:shots[3]].cpu().numpy()
+    np.testing.assert_array_equal(surv, seen["active"])
+    last_buf = st.x_a if (L - 1) % 2 == 0 else st.x_b
+    np.testing.assert_array_equal(final[surv], _f(last_buf[:shots[3]]))
 
 
 def test_single_shot_without_halting_is_the_plain_model():
