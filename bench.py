@@ -142,14 +142,21 @@ def _blocks_setup(cfg):
     st.params.keep_first_n, st.params.keep_last_n = QWEN_BLOCKS["first"], QWEN_BLOCKS["last"]
     final = torch.empty_like(x0)
 
-    def timed(shots, reps, warm):
-        """Mean seconds of one prefill under the schedule `shots` {block: rows kept after it}."""
+    def timed(shots, reps, warm, graph=False):
+        """Mean seconds of one prefill under the schedule `shots` {block: rows kept after it}: every launch
+        enqueued from the host, or (graph) the whole schedule captured once in a HIP graph and replayed."""
+        kw = dict(rope_theta=QWEN_BLOCKS["rope_theta"], final=final)
+        if graph:
+            gs = SS.GraphedSchedule(st, x0, weights, shots, **kw)
+            run = gs.replay
+        else:
+            run = lambda: SS.run_schedule(st, x0, weights, shots, **kw)
         for _ in range(warm):
-            SS.run_schedule(st, x0, weights, shots, rope_theta=QWEN_BLOCKS["rope_theta"], final=final)
+            run()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(reps):
-            res = SS.run_schedule(st, x0, weights, shots, rope_theta=QWEN_BLOCKS["rope_theta"], final=final)
+            res = run()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps, res
 
@@ -204,7 +211,8 @@ def run_schedule_sweep_bench(args, cfg, workload):
       qwen_vl_8k_extreme    one shot at the reduction ratios of the paper's vision-language table (75 % ... 99 %) on
                             an 8192-token prompt (Qwen2-VL-7B has the shapes of Qwen2.5-7B): short surviving
                             sequences, where launch gaps and occupancy, not the matrix pipe, set the time
-    A step = one prefill under the first schedule of the sweep; `value` is its prompt tokens/s."""
+    A step = one prefill under the first schedule of the sweep, replayed from a HIP graph that holds the whole
+    schedule (the launch-by-launch time is reported beside it); `value` is its prompt tokens/s."""
     from paper_2604_18103_amd import single_shot as SS
 
     L, m, start_block, first, last = (QWEN_BLOCKS[k] for k in ("L", "m", "start_block", "first", "last"))
@@ -219,16 +227,18 @@ def run_schedule_sweep_bench(args, cfg, workload):
     else:
         plans = [(f"{100 * c:.2f} % halted", [l0], c) for c in (0.75, 0.8889, 0.9375, 0.96, 0.99)]
     timed, block_flops = _blocks_setup(cfg)
-    t_full, _ = timed({}, max(2, args.steps // 2), 1)
+    t_full, _ = timed({}, max(2, args.steps // 2), 1, graph=True)
     rows = []
     for name, layers, c in plans:
         lengths = SS.schedule_lengths(N, L, {l: c for l in layers}, first, last)
         shots = {l: lengths[l + 1] for l in layers}
-        t, res = timed(shots, args.steps, max(1, args.warmup))
+        t_eager, res = timed(shots, args.steps, max(1, args.warmup))
         assert res["n_after"] == lengths[-1]
+        t, _ = timed(shots, args.steps, max(1, args.warmup), graph=True)
         flops = sum(block_flops(t_) for t_ in lengths)
         rows.append({"schedule": name, "decision_after_blocks": [l + 1 for l in layers], "ratio_per_shot": c,
                      "rows_per_block": sorted(set(lengths), reverse=True), "ms": 1e3 * t,
+                     "ms_launch_by_launch": 1e3 * t_eager,
                      "speedup_vs_full_model": t_full / t,
                      "speedup_of_executed_flops": L * block_flops(N) / flops,
                      "speedup_paper_formula": L * SS.block_cost(N, d, m) / sum(SS.block_cost(t_, d, m) for t_ in lengths),

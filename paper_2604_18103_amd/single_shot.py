@@ -37,6 +37,8 @@ class BlockState:
     x_b: torch.Tensor
     ffn_ws: torch.Tensor
     qkv_ws: torch.Tensor
+    idx0: torch.Tensor | None = None      # positions 0..N-1 of a full prompt, and two buffers for the
+    idx_spare: list | None = None         # survivors' positions after successive decisions
 
 
 def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda") -> BlockState:
@@ -59,20 +61,33 @@ def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda
 
 
 def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, rope_theta=None,
-                 final: torch.Tensor | None = None, on_block=None) -> dict:
+                 final: torch.Tensor | None = None, on_block=None, read_counts: bool = True) -> dict:
     """Run len(weights) blocks on x0 [N, d] (all N tokens active at the start). weights[l] = dict(w_q, w_k, w_v,
     w_o, w_gate_up, w_down) of device tensors. `shots` maps a block index to the number of rows kept after that
     block: one entry is the single-shot schedule of Alg. 1, several entries are a multi-shot schedule (every
     decision ranks the rows still active by their Delta_attn in that block), none is the full model. `final`
     [N, d] receives every token's last state. `on_block(l, x_in, idx, n, st, x_out)` is called after every block
-    (after a device synchronisation) for checks. One 4-byte read-back per decision sizes the later launches.
-    Returns {n_after, final, idx}."""
+    (after a device synchronisation) for checks. One 4-byte read-back per decision sizes the later launches;
+    with read_counts = False the host does not wait for it and takes the requested count instead (TopK keeps
+    exactly that many rows), so the whole schedule is enqueued without a host synchronisation and can be
+    captured in a HIP graph (capture_schedule). Returns {n_after, final, idx}."""
     p, buf = st.params, st.buf
     N, d = x0.shape
+    if not read_counts:
+        if on_block is not None:
+            raise ValueError("on_block needs the host to wait for every block: use read_counts=True")
+        cur = N
+        for l in sorted(shots):
+            # TopK never halts a protected row: a smaller request would keep more rows than asked for
+            if int(shots[l]) < min(cur, p.keep_first_n + p.keep_last_n) or int(shots[l]) < 0:
+                raise ValueError(f"block {l}: cannot keep {shots[l]} of {cur} rows with the protected ranks")
+            cur = min(int(shots[l]), cur)
     if final is None:
         final = torch.empty_like(x0)
-    idx = torch.arange(N, dtype=torch.int32, device=x0.device)
-    idx_spare = [torch.empty_like(idx), torch.empty_like(idx)]
+    if st.idx0 is None or st.idx0.numel() != N:
+        st.idx0 = torch.arange(N, dtype=torch.int32, device=x0.device)
+        st.idx_spare = [torch.empty_like(st.idx0), torch.empty_like(st.idx0)]
+    idx, idx_spare = st.idx0, st.idx_spare
     n_shot = 0
     x, n = x0, N
     spare = [st.x_a, st.x_b]
@@ -93,7 +108,7 @@ def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, r
             n_shot += 1
             B.dash_compact(p, buf.halt_mask, None, old_idx, buf.x_next, n, x_out, idx, buf.n_active_out,
                            buf.workspace)
-            n_new = int(buf.n_active_out.item())          # the one host read of this decision
+            n_new = int(buf.n_active_out.item()) if read_counts else min(int(shots[l]), n)   # the one host read
             if on_block is not None:
                 on_block(l, x, old_idx, n, st, buf.x_next)
             x, n = x_out, n_new
@@ -107,6 +122,31 @@ def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, r
             x = x_out
     B.dash_scatter_rows(x, idx, None, 0, n, d, p.dtype, N, final)
     return {"n_after": n, "final": final, "idx": idx}
+
+
+class GraphedSchedule:
+    """A whole schedule (every block, every decision, the final scatter) captured once in a HIP graph and
+    replayed with one launch: with a short surviving sequence a block is a dozen launches of a few microseconds
+    each, and enqueueing them one by one from the host takes longer than running them. The graph reads x0 and
+    the weights at the addresses given at capture and writes `final`; new prompt contents are copied into x0
+    before a replay. Valid while the BlockState, x0, the weights and `final` are alive and not reallocated."""
+
+    def __init__(self, st: BlockState, x0: torch.Tensor, weights: list, shots: dict, rope_theta=None,
+                 final: torch.Tensor | None = None):
+        self.final = torch.empty_like(x0) if final is None else final
+        args = dict(rope_theta=rope_theta, final=self.final, read_counts=False)
+        run_schedule(st, x0, weights, shots, **args)           # eager once: one-time set-up of the library
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.result = run_schedule(st, x0, weights, shots, **args)
+        self.n_after = self.result["n_after"]
+        self.idx = self.result["idx"]
+        self._keep = (st, x0, weights)
+
+    def replay(self) -> dict:
+        self.graph.replay()
+        return self.result
 
 
 def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | None, k_keep: int,

@@ -269,6 +269,53 @@ def test_multi_shot_schedule_teacher_forced_against_oracle():
     np.testing.assert_array_equal(final[surv], _f(last_buf[:shots[3]]))
 
 
+def test_graphed_schedule_replays_match_eager_runs():
+    """A two-shot schedule captured in a HIP graph: every replay, with eager work of the same library and
+    synchronisations in between and with the prompt's contents changed in place, equals the eager run on the same
+    contents bit for bit (all kernels are deterministic)."""
+    N, d, m, L, theta = 600, 256, 512, 4, 1.0e6
+    cfg = I.LayerConfig("blocks_graph", "bf16", N, N, d, 4, 2, 64, 0.4, seed=73)
+    Wdev = []
+    for l in range(L):
+        w = I.make_projection_weights(cfg, l)
+        w.update(I.make_ffn_weights(cfg, l, m))
+        dw = {k: _dev(w[k]) for k in ("w_q", "w_k", "w_v", "w_o", "w_down")}
+        dw["w_gate_up"] = B.interleave_gate_up(_dev(w["w_gate"]), _dev(w["w_up"]))
+        Wdev.append(dw)
+    shots = {0: 400, 2: 150}
+    xa = _dev(I.make_hidden(cfg))
+    xb = _dev(I.make_hidden(I.scaled(cfg, N, N=N, seed=74)))
+    st_e = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
+    st_g = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
+    for st in (st_e, st_g):
+        st.params.keep_first_n, st.params.keep_last_n = 8, 4
+
+    def eager(x):
+        r = SS.run_schedule(st_e, x, Wdev, shots, rope_theta=theta)
+        torch.cuda.synchronize()
+        assert r["n_after"] == 150
+        return r["final"].clone(), r["idx"][:150].clone()
+
+    fa, ia = eager(xa)
+    fb, ib = eager(xb)
+    assert not torch.equal(fa, fb) and not torch.equal(ia, ib)
+    x_in = xa.clone()
+    gs = SS.GraphedSchedule(st_g, x_in, Wdev, shots, rope_theta=theta)
+    assert gs.n_after == 150
+    for contents, (want_f, want_i) in ((xa, (fa, ia)), (xb, (fb, ib)), (xb, (fb, ib)), (xa, (fa, ia))):
+        x_in.copy_(contents)
+        gs.final.zero_()
+        gs.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(gs.final, want_f)
+        assert torch.equal(gs.idx[:150], want_i)
+        assert int(st_g.buf.n_active_out.item()) == 150
+        f2, _ = eager(xb if contents is xa else xa)          # eager work between the replays
+        assert torch.equal(f2, fb if contents is xa else fa)
+    with pytest.raises(ValueError):
+        SS.run_schedule(st_g, x_in, Wdev, {0: 5}, rope_theta=theta, read_counts=False)
+
+
 def test_single_shot_without_halting_is_the_plain_model():
     """l_s = None: every block on every row; the result is the last block's output at every position."""
     N, d, m, L = 200, 128, 128, 2
