@@ -261,6 +261,78 @@ def run_schedule_sweep_bench(args, cfg, workload):
         "schedules": rows}))
 
 
+def run_aux_kernels_bench(args, cfg):
+    """The HBM-bound kernels beside the layer, each launched 50 times back to back between two events on operands
+    that rotate over three buffers (more than the last-level cache holds): the standalone score of Eq. 2 from a
+    stored delta, the block-level signal of the ablation (Sec. 5.4), the scatter of halted rows, the rotary
+    embedding, and the TopK decision on given scores (latency-bound: microseconds only). Sizes of the headline
+    workload (16384 active rows of a 32768-token prompt, hidden 3584). `value` is the mean fraction of the HBM peak
+    over the four bandwidth-bound kernels."""
+    import torch
+    from paper_2604_18103_amd import binding as B
+
+    n, N, d, Hq, Hkv, dh = cfg.n, cfg.N, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    p = B.make_params(d, Hq, Hkv, dh, causal=True, rule=B.RULE_TOPK, k_keep=n - int(cfg.halt_frac * n))
+    g = torch.Generator(device="cuda").manual_seed(cfg.seed)
+    bf = torch.bfloat16
+    rnd = lambda *shape: torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+    xs = [rnd(n, d).to(bf) for _ in range(3)]
+    ys = [(xs[i].float() + 0.05 * rnd(n, d)).to(bf) for i in range(3)]
+    deltas = [rnd(n, d) for _ in range(3)]
+    fulls = [torch.empty((N, d), dtype=bf, device="cuda") for _ in range(3)]
+    qs = [rnd(n, Hq, dh).to(bf) for _ in range(3)]
+    ks = [rnd(n, Hkv, dh).to(bf) for _ in range(3)]
+    idx = torch.sort(torch.randperm(N, generator=g, device="cuda")[:n]).values.to(torch.int32)
+    scores = torch.empty((n,), dtype=torch.float32, device="cuda")
+    halt = torch.empty((n,), dtype=torch.uint8, device="cuda")
+    counts = torch.empty(((n + 63) // 64,), dtype=torch.int32, device="cuda")
+    ws = torch.empty((256 + 4 * ((n + 63) // 64) + 64,), dtype=torch.uint8, device="cuda")
+    reps = 50
+
+    def timed(fn):
+        for i in range(5):
+            fn(i)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3     # microseconds per launch
+
+    cases = [
+        ("score_rows_kernel (Eq. 2 from stored fp32 delta and x)", n * d * (4 + 2) + 4 * n,
+         lambda i: B.dash_score_rows(deltas[i % 3], xs[i % 3], n, d, B.DASH_BF16, B.SCORE_REL, scores)),
+        ("score_diff_rows_kernel (block-level signal)", n * d * (2 + 2) + 4 * n,
+         lambda i: B.dash_score_diff_rows(ys[i % 3], xs[i % 3], n, d, B.DASH_BF16, B.SCORE_REL, scores)),
+        ("scatter_rows_kernel (all rows to their original positions)", 2 * n * d * 2 + 4 * n,
+         lambda i: B.dash_scatter_rows(xs[i % 3], idx, None, 0, n, d, B.DASH_BF16, N, fulls[i % 3])),
+        ("rope_qk_kernel (q and k in place)", 2 * n * (Hq + Hkv) * dh * 2 + 4 * n,
+         lambda i: B.dash_rope_qk(p, qs[i % 3], ks[i % 3], idx, n, 1.0e6)),
+    ]
+    rows = []
+    for name, nbytes, fn in cases:
+        us = timed(fn)
+        rows.append({"kernel": name, "bytes": nbytes, "us": us, "GB/s": nbytes / us / 1e3,
+                     "frac_of_hbm_peak": nbytes / us / 1e3 / HBM_PEAK_GBS})
+    B.dash_score_rows(deltas[0], xs[0], n, d, B.DASH_BF16, B.SCORE_REL, scores)
+    us_topk = timed(lambda i: B.dash_decide_topk(p, scores, n, False, halt, counts, ws))
+    rows.append({"kernel": "topk_select_kernel + topk_flag_kernel (decision on given scores, 2 launches)",
+                 "bytes": 4 * n * 2 + n, "us": us_topk, "GB/s": None, "frac_of_hbm_peak": None})
+    mean_frac = sum(r["frac_of_hbm_peak"] for r in rows[:4]) / 4
+    print(json.dumps({
+        "metric": "mean fraction of the HBM peak over the bandwidth-bound kernels beside the layer",
+        "value": mean_frac, "unit": "fraction of 8 TB/s", "n_gpus": 1, "steps": reps, "warmup": 5,
+        "ms_per_step": sum(r["us"] for r in rows) * 1e-3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": "aux_kernels", "N": N, "n_active": n, "hidden": d, "q_heads": Hq, "kv_heads": Hkv,
+                   "head_dim": dh},
+        "roofline": {"bound": "hbm", "achieved": mean_frac * HBM_PEAK_GBS, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": mean_frac, "traffic": None},
+        "kernels": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -270,7 +342,8 @@ def main():
                     help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads; qwen_32k_chain is "
                          "the 8-layer chain), qwen_32k_single_shot (28 full blocks, one halting decision), "
                          "qwen_32k_multi_shot (1- to 4-shot schedules under one budget) or qwen_vl_8k_extreme "
-                         "(one shot, 75 % to 99 % of the tokens halted)")
+                         "(one shot, 75 % to 99 % of the tokens halted), or aux_kernels (the bandwidth-bound kernels "
+                         "beside the layer, one by one)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run device-to-device copies of this many MiB (a plain copy kernel of known "
@@ -292,6 +365,9 @@ def main():
     B.lib()  # fail loudly if the HIP library is missing
     if args.workload == "qwen_32k_single_shot":
         run_single_shot_bench(args, I.CONFIGS["qwen_32k_chain"])
+        return
+    if args.workload == "aux_kernels":
+        run_aux_kernels_bench(args, I.CONFIGS["qwen_32k_half"])
         return
     if args.workload == "qwen_32k_multi_shot":
         run_schedule_sweep_bench(args, I.CONFIGS["qwen_32k_chain"], args.workload)

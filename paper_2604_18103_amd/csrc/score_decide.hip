@@ -97,9 +97,9 @@ constexpr int kSelectThreads = 1024;
 __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, int keep_low,
     TopkState* __restrict__ st, int32_t* __restrict__ tie_counts) {
-    __shared__ int hist[256];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_remaining;
+    __shared__ int hist[256], hist_suf[256], wave_tot[4];
+    __shared__ uint32_t sh_prefix, sh_prefix_next;
+    __shared__ int sh_remaining, sh_remaining_next;
     const int tid = threadIdx.x;
     const int lo = min(n_first, n), hi = max(lo, n - n_last);  // candidates are rows [lo, hi)
     const int n_cand = hi - lo;
@@ -120,26 +120,70 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
         for (int c = tid; c < n_chunks; c += kSelectThreads) tie_counts[c] = 0;
         return;
     }
+    const int lane_s = tid % kWave, wave_s = tid / kWave;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
         for (int b = tid; b < 256; b += kSelectThreads) hist[b] = 0;
         __syncthreads();
         const uint32_t prefix = sh_prefix;
         const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int r = lo + tid; r < hi; r += kSelectThreads) {
-            const uint32_t key = rank_key(scores[r], keep_low);
-            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 0xFFu], 1);
+        for (int r0 = lo; r0 < hi; r0 += kSelectThreads) {
+            const int r = r0 + tid;
+            uint32_t bin = 0;
+            bool mine = false;
+            if (r < hi) {
+                const uint32_t key = rank_key(scores[r], keep_low);
+                mine = (key & hi_mask) == prefix;
+                bin = (key >> shift) & 0xFFu;
+            }
+            // Scores of one layer share a few exponents, so most lanes of a wave hit the same one or two
+            // bins in the first pass: those are counted with one ballot and one add per bin, the rest add
+            // on their own (integer adds: the order does not matter).
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const unsigned long long todo = __ballot(mine);
+                if (todo == 0ull) break;
+                const int leader = __ffsll((long long)todo) - 1;
+                const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
+                const unsigned long long same = __ballot(mine && bin == lb);
+                if (lane_s == leader) atomicAdd(&hist[lb], (int)__popcll(same));
+                if (bin == lb) mine = false;
+            }
+            if (mine) atomicAdd(&hist[bin], 1);
+        }
+        __syncthreads();
+        // The bin that holds the remaining-th largest key: the largest b with (keys in bins >= b) >= remaining.
+        // Suffix sums over the 256 bins by the first four waves (bin = thread), then the one thread whose bin
+        // crosses the count publishes the new prefix.
+        if (tid < 256) {
+            const int v = hist[tid];
+            int suf = v;  // sum over bins tid .. end of this wave's 64 bins
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int t = __shfl_down(suf, o);
+                if (lane_s + o < kWave) suf += t;
+            }
+            if (lane_s == 0) wave_tot[wave_s] = suf;
+            hist_suf[tid] = suf;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            int incl = hist_suf[tid];
+            for (int w = wave_s + 1; w < 4; ++w) incl += wave_tot[w];
+            const int excl = incl - hist[tid];
+            const int remaining = sh_remaining;
+            // exactly one bin satisfies excl < remaining <= incl when the candidates under the prefix are at
+            // least `remaining` (they are); bin 0 also takes the (unreachable) case of too few
+            const bool crossing = excl < remaining && (remaining <= incl || tid == 0);
+            if (crossing) {
+                sh_prefix_next = prefix | ((uint32_t)tid << shift);
+                sh_remaining_next = remaining - excl;
+            }
         }
         __syncthreads();
         if (tid == 0) {
-            int remaining = sh_remaining;
-            int b = 255;
-            for (; b > 0; --b) {
-                if (hist[b] >= remaining) break;
-                remaining -= hist[b];
-            }
-            sh_prefix = prefix | ((uint32_t)b << shift);
-            sh_remaining = remaining;
+            sh_prefix = sh_prefix_next;
+            sh_remaining = sh_remaining_next;
         }
         __syncthreads();
     }
