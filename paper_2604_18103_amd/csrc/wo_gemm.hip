@@ -487,14 +487,43 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         *reinterpret_cast<float2*>(partials + ((size_t)grp * M + row) * 2) = make_float2(sd, sx);
 }
 
-// h = x / sqrt(mean(x^2) + 1e-6), unit gain; one wave per row.
+// h = x / sqrt(mean(x^2) + 1e-6), unit gain; one wave per row. Rows of up to 512 * CH elements are held in
+// registers between the two passes (one read of x); longer rows are read twice (CH = 0).
+template <int CH>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__ x, int n, int d,
                                                       __bf16* __restrict__ hout) {
     const int row = (blockIdx.x * blockDim.x + threadIdx.x) / kWave;
     const int lane = threadIdx.x % kWave;
     if (row >= n) return;
     const __bf16* xr = x + (size_t)row * d;
+    __bf16* hr = hout + (size_t)row * d;
     float ss = 0.f;
+    if (CH > 0) {
+        bf16x8 v[CH > 0 ? CH : 1];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = (i * kWave + lane) * 8;
+            if (c < d) {
+                v[i] = *reinterpret_cast<const bf16x8*>(xr + c);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ss = fmaf((float)v[i][e], (float)v[i][e], ss);
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
+        const float inv = 1.0f / sqrtf(ss / (float)d + 1e-6f);
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int c = (i * kWave + lane) * 8;
+            if (c < d) {
+                bf16x8 ov;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) ov[e] = (__bf16)((float)v[i][e] * inv);
+                *reinterpret_cast<bf16x8*>(hr + c) = ov;
+            }
+        }
+        return;
+    }
     for (int c = lane * 8; c < d; c += kWave * 8) {
         const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c);
 #pragma unroll
@@ -503,7 +532,6 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) ss += __shfl_xor(ss, off);
     const float inv = 1.0f / sqrtf(ss / (float)d + 1e-6f);
-    __bf16* hr = hout + (size_t)row * d;
     for (int c = lane * 8; c < d; c += kWave * 8) {
         const bf16x8 v = *reinterpret_cast<const bf16x8*>(xr + c);
         bf16x8 ov;
@@ -511,6 +539,16 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const __bf16* __restrict__
         for (int e = 0; e < 8; ++e) ov[e] = (__bf16)((float)v[e] * inv);
         *reinterpret_cast<bf16x8*>(hr + c) = ov;
     }
+}
+
+static void launch_rmsnorm(const __bf16* x, int n, int d, __bf16* h, hipStream_t s) {
+    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
+    if (d <= 512 * 4)
+        hipLaunchKernelGGL(rmsnorm_kernel<4>, dim3(blocks), dim3(256), 0, s, x, n, d, h);
+    else if (d <= 512 * 8)
+        hipLaunchKernelGGL(rmsnorm_kernel<8>, dim3(blocks), dim3(256), 0, s, x, n, d, h);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<0>, dim3(blocks), dim3(256), 0, s, x, n, d, h);
 }
 
 int norm_partials_per_row(int d, int dtype) {
@@ -643,8 +681,7 @@ dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const v
     char* split_ws = reinterpret_cast<char*>(partials) +
                      up256((size_t)n * norm_partials_per_row(p.d, p.dtype) * 2 * sizeof(float));
     const size_t split_bytes = max(gemm_splitk_bytes(n, p.d, 2 * m), gemm_splitk_bytes(n, m, p.d));
-    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(blocks), dim3(256), 0, s, (const __bf16*)x, n, p.d, h);
+    launch_rmsnorm((const __bf16*)x, n, p.d, h, s);
     dash_status st = launch_gemm<EPI_SWIGLU>(h, (const __bf16*)w_gate_up, n, p.d, 2 * m, nullptr, act, nullptr,
                                              nullptr, split_ws, split_bytes, s);
     if (st != DASH_OK) return st;
@@ -662,8 +699,7 @@ dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const 
                                size_t split_bytes, hipStream_t s) {
     if (n == 0) return DASH_OK;
     const int d = p.d, Dq = p.n_q_heads * p.head_dim, Dkv = p.n_kv_heads * p.head_dim;
-    const int blocks = (int)(((size_t)n * kWave + 255) / 256);
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3(blocks), dim3(256), 0, s, (const __bf16*)x, n, d, (__bf16*)hbuf);
+    launch_rmsnorm((const __bf16*)x, n, d, (__bf16*)hbuf, s);
     const __bf16* h = (const __bf16*)hbuf;
     dash_status st = launch_gemm<EPI_STORE>(h, (const __bf16*)w_q, n, d, Dq, nullptr, (__bf16*)q, nullptr, nullptr,
                                             split_ws, split_bytes, s);

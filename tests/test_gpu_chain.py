@@ -19,8 +19,10 @@ def _dev(a):
     return B.to_device(a, B.DASH_BF16)
 
 
-def test_rmsnorm_qkv_matches_oracle():
-    cfg = I.scaled(CFG, 333, N=333)
+@pytest.mark.parametrize("d", [512, 2560, 4160], ids=lambda v: "d%d" % v)
+def test_rmsnorm_qkv_matches_oracle(d):
+    """Rows of 512, 2560 and 4160 elements: held in registers (4 or 8 chunks of 512) or read twice."""
+    cfg = I.scaled(CFG, 333 if d == 512 else 70, N=333, d=d)
     x = I.make_hidden(cfg)
     W = I.make_projection_weights(cfg, 0)
     p = P.params_for(cfg)
