@@ -74,8 +74,10 @@ def run_chain_bench(args, cfg, n_layers=8):
     from paper_2604_18103_amd import chain as CH
     from paper_2604_18103_amd import inputs as I
 
-    weights = [{k: B.to_device(v, B.DASH_BF16) for k, v in I.make_projection_weights(cfg, l).items()}
-               for l in range(n_layers)]
+    weights = []
+    for l in range(n_layers):
+        W = {k: B.to_device(v, B.DASH_BF16) for k, v in I.make_projection_weights(cfg, l).items()}
+        weights.append({"w_qkv": B.concat_qkv(W["w_q"], W["w_k"], W["w_v"]), "w_o": W["w_o"]})
     x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)
     idx0 = torch.from_numpy(I.make_active_idx(cfg.N, cfg.n, cfg.seed)).cuda()
     state = CH.alloc_chain(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n)
@@ -134,7 +136,7 @@ def _blocks_setup(cfg):
 
     weights = []
     for _ in range(L):
-        weights.append(dict(w_q=rnd(d, Hq * dh, d), w_k=rnd(d, Hkv * dh, d), w_v=rnd(d, Hkv * dh, d),
+        weights.append(dict(w_qkv=B.concat_qkv(rnd(d, Hq * dh, d), rnd(d, Hkv * dh, d), rnd(d, Hkv * dh, d)),
                             w_o=rnd(Hq * dh, d, d), w_down=rnd(m, d, m),
                             w_gate_up=B.interleave_gate_up(rnd(d, m, d), rnd(d, m, d))))
     x0 = B.to_device(I.make_hidden(cfg), B.DASH_BF16)

@@ -178,6 +178,13 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params *params, const void *x, con
                              const void *w_k, const void *w_v, int32_t n, void *q, void *k, void *v,
                              void *h_scratch, void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* The same front end as ONE product over the concatenated weight w_qkv = [w_q | w_k | w_v], device
+ * [d, (Hq + 2 Hkv) * dh] row-major: the normalised rows are read once instead of three times and the narrow k and
+ * v projections no longer run as launches of their own. Outputs, scratch and workspace as in dash_rmsnorm_qkv. */
+dash_status dash_rmsnorm_qkv_fused(const dash_layer_params *params, const void *x, const void *w_qkv, int32_t n,
+                                   void *q, void *k, void *v, void *h_scratch, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream);
+
 /* Rotary position embedding of the backbone (Qwen2.5 / Llama-3, Sec. 4.1) applied in place to q [n,Hq,dh] and
  * k [n,Hkv,dh] (bf16, device), with each row's ORIGINAL position active_idx[t]: the compacted active sequence
  * of Sec. 3.4 keeps the position ids, so this is where active_idx matters numerically. "Rotate-half" pairing:

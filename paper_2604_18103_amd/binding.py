@@ -72,6 +72,8 @@ def lib() -> C.CDLL:
     L.dash_compact.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
     L.dash_score_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_rmsnorm_qkv.argtypes = [pp, _vp, _vp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.dash_rmsnorm_qkv_fused.argtypes = [pp, _vp, _vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.dash_rmsnorm_qkv_fused.restype = C.c_int
     L.dash_qkv_workspace_bytes.restype = C.c_size_t
     L.dash_qkv_workspace_bytes.argtypes = [pp, C.c_int32]
     L.dash_rope_qk.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_double, _vp]
@@ -278,6 +280,17 @@ def dash_rmsnorm_qkv(params, x, w_q, w_k, w_v, n, q, k, v, h_scratch, workspace=
     ws_n = workspace.numel() if workspace is not None else 0
     _check(lib().dash_rmsnorm_qkv(C.byref(params), _p(x), _p(w_q), _p(w_k), _p(w_v), int(n), _p(q), _p(k),
                                   _p(v), _p(h_scratch), _p(workspace), ws_n, _stream()), "dash_rmsnorm_qkv")
+
+
+def concat_qkv(w_q: torch.Tensor, w_k: torch.Tensor, w_v: torch.Tensor) -> torch.Tensor:
+    """[w_q | w_k | w_v] as one contiguous [d, (Hq + 2 Hkv) * dh] weight for dash_rmsnorm_qkv_fused."""
+    return torch.cat([w_q, w_k, w_v], dim=1).contiguous()
+
+
+def dash_rmsnorm_qkv_fused(params, x, w_qkv, n, q, k, v, h_scratch, workspace=None) -> None:
+    ws_n = workspace.numel() if workspace is not None else 0
+    _check(lib().dash_rmsnorm_qkv_fused(C.byref(params), _p(x), _p(w_qkv), int(n), _p(q), _p(k), _p(v),
+                                        _p(h_scratch), _p(workspace), ws_n, _stream()), "dash_rmsnorm_qkv_fused")
 
 
 def dash_validate_active_idx(active_idx, n, N, violations) -> None:

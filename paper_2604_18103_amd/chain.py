@@ -44,7 +44,7 @@ def alloc_chain(d, n_q_heads, n_kv_heads, head_dim, n_capacity, device="cuda") -
 
 def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0: int, weights: list,
               halt_frac: float, on_layer=None, time_layers=False, rope_theta=None) -> list:
-    """Run len(weights) layers. weights[l] = dict(w_q, w_k, w_v, w_o) of device tensors.
+    """Run len(weights) layers. weights[l] = dict(w_q, w_k, w_v, w_o) or dict(w_qkv, w_o) of device tensors.
     Returns per-layer dicts {n_in, n_out, ms}. `on_layer(l, x, idx, n, q, k, v, buf)` is called after each
     layer (after a device synchronisation) with that layer's inputs and outputs, for checks.
     With rope_theta, q and k get the backbone's rotary embedding at the tokens' original positions."""
@@ -57,7 +57,10 @@ def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0
         if time_layers:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, state.q, state.k, state.v, state.h, state.qkv_ws)
+        if "w_qkv" in W:      # one product over the concatenated weight
+            B.dash_rmsnorm_qkv_fused(p, x, W["w_qkv"], n, state.q, state.k, state.v, state.h, state.qkv_ws)
+        else:
+            B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, state.q, state.k, state.v, state.h, state.qkv_ws)
         if rope_theta is not None:
             B.dash_rope_qk(p, state.q, state.k, idx, n, rope_theta)
         B.dash_attn_layer(p, x, state.q, state.k, state.v, W["w_o"], idx, n, buf)

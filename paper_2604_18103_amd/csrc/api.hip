@@ -251,6 +251,23 @@ dash_status dash_rmsnorm_qkv(const dash_layer_params* p, const void* x, const vo
                               workspace ? workspace_bytes : 0, (hipStream_t)hip_stream);
 }
 
+dash_status dash_rmsnorm_qkv_fused(const dash_layer_params* p, const void* x, const void* w_qkv, int32_t n, void* q,
+                                   void* k, void* v, void* h_scratch, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (p->dtype != DASH_BF16) return DASH_ERR_UNSUPPORTED;
+    if (p->d % 64 != 0) return DASH_ERR_UNSUPPORTED;  // K step of the projection GEMM
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n == 0) return DASH_OK;
+    if (!x || !w_qkv || !q || !k || !v || !h_scratch) return DASH_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(w_qkv) || !aligned16(q) || !aligned16(k) || !aligned16(v) ||
+        !aligned16(h_scratch) || !aligned16(workspace))
+        return DASH_ERR_INVALID_ARG;
+    return launch_rmsnorm_qkv_fused(*p, x, w_qkv, n, q, k, v, h_scratch, workspace, workspace ? workspace_bytes : 0,
+                                    (hipStream_t)hip_stream);
+}
+
 size_t dash_ffn_workspace_bytes(const dash_layer_params* p, int32_t n_capacity, int32_t m) {
     if (check_params(p) != DASH_OK || n_capacity < 0 || m <= 0) return 0;
     return ffn_workspace_bytes(*p, n_capacity, m);

@@ -59,6 +59,8 @@ size_t qkv_workspace_bytes(const dash_layer_params& p, int n);
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
                                const void* w_v, int n, void* q, void* k, void* v, void* h, void* split_ws,
                                size_t split_bytes, hipStream_t s);
+dash_status launch_rmsnorm_qkv_fused(const dash_layer_params& p, const void* x, const void* w_qkv, int n, void* q,
+                                     void* k, void* v, void* h, void* split_ws, size_t split_bytes, hipStream_t s);
 // score_decide.hip
 size_t decide_workspace_bytes();
 dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,

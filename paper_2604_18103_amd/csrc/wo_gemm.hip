@@ -138,7 +138,23 @@ __device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(
 // N / 2 columns per row.
 // EPI_SPLITK: the workgroup covers only the K steps of split blockIdx.y and writes its fp32 accumulators to
 // f32_out[split][M][N]; a reduction kernel adds the splits in order and applies one of the other epilogues.
-enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1, EPI_SWIGLU = 2, EPI_SPLITK = 3 };
+// EPI_QKV: a plain store whose columns are routed to three outputs (the q, k and v projections as one product
+// over the concatenated weight).
+enum { EPI_RESIDUAL_NORM = 0, EPI_STORE = 1, EPI_SWIGLU = 2, EPI_SPLITK = 3, EPI_QKV = 4 };
+
+// Output routing of EPI_QKV: columns [0, Dq) go to `out` (row stride Dq), [Dq, Dq + Dkv) to k and the rest to v
+// (row stride Dkv). Dq and Dkv are multiples of 8, so the 8 columns a lane stores never straddle two outputs.
+struct QkvOut {
+    __bf16* k;
+    __bf16* v;
+    int Dq, Dkv;
+};
+__device__ __forceinline__ __bf16* qkv_dst(__bf16* q, const QkvOut& o, int row, int col) {
+    if (col < o.Dq) return q + (size_t)row * o.Dq + col;
+    col -= o.Dq;
+    if (col < o.Dkv) return o.k + (size_t)row * o.Dkv + col;
+    return o.v + (size_t)row * o.Dkv + (col - o.Dkv);
+}
 
 // MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
 // grid: when the 256-row tiles do not fill a whole number of rounds over the compute units, the tiles of
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                                                                  float* __restrict__ partials,
                                                                  float* __restrict__ f32_out,  // delta (debug) or split sums
                                                                  int n_mtiles, int first_tile,
-                                                                 int ksteps_per_split) {
+                                                                 int ksteps_per_split, QkvOut qkv) {
     constexpr int BM = 64 * MB;   // rows of this workgroup's tile
     constexpr int WM = 32 * MB;   // rows of a wave's tile
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
@@ -393,7 +409,8 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                 bf16x8 ov;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) ov[e] = (__bf16)dv[e];
-                *reinterpret_cast<bf16x8*>(out + (size_t)gm * N + gn_e) = ov;
+                __bf16* dst = EPI == EPI_QKV ? qkv_dst(out, qkv, gm, gn_e) : out + (size_t)gm * N + gn_e;
+                *reinterpret_cast<bf16x8*>(dst) = ov;
             }
         }
         __syncthreads();
@@ -406,7 +423,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ sums, int S, int M, int N,
                                                             const __bf16* __restrict__ x, __bf16* __restrict__ out,
-                                                            float* __restrict__ partials) {
+                                                            float* __restrict__ partials, QkvOut qkv) {
     const int lane = threadIdx.x % kWave;
     const int wave_global = (int)((blockIdx.x * (size_t)blockDim.x + threadIdx.x) / kWave);
     if (EPI == EPI_SWIGLU) {
@@ -454,12 +471,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
             }
         }
     }
-    if (EPI == EPI_STORE) {
+    if (EPI == EPI_STORE || EPI == EPI_QKV) {
         if (ok) {
             bf16x8 ov;
 #pragma unroll
             for (int e = 0; e < 8; ++e) ov[e] = (__bf16)acc[e];
-            *reinterpret_cast<bf16x8*>(out + (size_t)row * N + col) = ov;
+            __bf16* dst = EPI == EPI_QKV ? qkv_dst(out, qkv, row, col) : out + (size_t)row * N + col;
+            *reinterpret_cast<bf16x8*>(dst) = ov;
         }
         return;
     }
@@ -599,7 +617,7 @@ size_t gemm_splitk_bytes(int M_cap, int K, int N) {
 template <int EPI>
 static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
                                __bf16* out, float* partials, float* delta_dbg, void* split_ws, size_t split_bytes,
-                               hipStream_t s) {
+                               hipStream_t s, QkvOut qkv = QkvOut{nullptr, nullptr, 0, 0}) {
     static const hipError_t attr4 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                                          (int)kGemmSmemBytes);
@@ -621,11 +639,11 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
             parts = (ksteps + per - 1) / per;  // every part has at least one K step
             float* sums = reinterpret_cast<float*>(split_ws);
             hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(tiles, parts), dim3(kGThreads), kGemmSmemBytes, s,
-                               A, B, M, K, N, nullptr, nullptr, nullptr, sums, mt, 0, per);
+                               A, B, M, K, N, nullptr, nullptr, nullptr, sums, mt, 0, per, qkv);
             const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
             const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
             hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((waves * kWave + 255) / 256)), dim3(256), 0,
-                               s, sums, parts, M, N, x, out, partials);
+                               s, sums, parts, M, N, x, out, partials, qkv);
             return launch_status();
         }
     }
@@ -634,10 +652,10 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
     const int full = tiles - rest;
     if (full > 0)
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
-                           out, partials, delta_dbg, mt, 0, ksteps);
+                           out, partials, delta_dbg, mt, 0, ksteps, qkv);
     if (rest > 0)
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
-                           x, out, partials, delta_dbg, mt, full, ksteps);
+                           x, out, partials, delta_dbg, mt, full, ksteps, qkv);
     return launch_status();
 }
 
@@ -691,7 +709,9 @@ dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const v
 
 size_t qkv_workspace_bytes(const dash_layer_params& p, int n) {
     if (p.dtype != DASH_BF16) return 0;
-    return gemm_splitk_bytes(n, p.d, p.n_q_heads * p.head_dim);  // the widest of the three projections
+    const int Dq = p.n_q_heads * p.head_dim, Dkv = p.n_kv_heads * p.head_dim;
+    // the widest of the three separate projections, or the one product over the concatenated weight
+    return max(gemm_splitk_bytes(n, p.d, Dq), gemm_splitk_bytes(n, p.d, Dq + 2 * Dkv));
 }
 
 dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const void* w_q, const void* w_k,
@@ -709,6 +729,18 @@ dash_status launch_rmsnorm_qkv(const dash_layer_params& p, const void* x, const 
     if (st != DASH_OK) return st;
     return launch_gemm<EPI_STORE>(h, (const __bf16*)w_v, n, d, Dkv, nullptr, (__bf16*)v, nullptr, nullptr, split_ws,
                                   split_bytes, s);
+}
+
+// The same front end as one product over w_qkv = [w_q | w_k | w_v] ([d, Dq + 2 Dkv]): one pass over the
+// normalised rows instead of three, and no launches that fill a fraction of the chip for the narrow k and v.
+dash_status launch_rmsnorm_qkv_fused(const dash_layer_params& p, const void* x, const void* w_qkv, int n, void* q,
+                                     void* k, void* v, void* hbuf, void* split_ws, size_t split_bytes,
+                                     hipStream_t s) {
+    if (n == 0) return DASH_OK;
+    const int d = p.d, Dq = p.n_q_heads * p.head_dim, Dkv = p.n_kv_heads * p.head_dim;
+    launch_rmsnorm((const __bf16*)x, n, d, (__bf16*)hbuf, s);
+    return launch_gemm<EPI_QKV>((const __bf16*)hbuf, (const __bf16*)w_qkv, n, d, Dq + 2 * Dkv, nullptr, (__bf16*)q,
+                                nullptr, nullptr, split_ws, split_bytes, s, QkvOut{(__bf16*)k, (__bf16*)v, Dq, Dkv});
 }
 
 }  // namespace dash

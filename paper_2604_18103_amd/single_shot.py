@@ -63,7 +63,7 @@ def alloc_blocks(d, n_q_heads, n_kv_heads, head_dim, m, n_capacity, device="cuda
 def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, rope_theta=None,
                  final: torch.Tensor | None = None, on_block=None, read_counts: bool = True) -> dict:
     """Run len(weights) blocks on x0 [N, d] (all N tokens active at the start). weights[l] = dict(w_q, w_k, w_v,
-    w_o, w_gate_up, w_down) of device tensors. `shots` maps a block index to the number of rows kept after that
+    w_o, w_gate_up, w_down) of device tensors (w_qkv = binding.concat_qkv(w_q, w_k, w_v) may replace the three). `shots` maps a block index to the number of rows kept after that
     block: one entry is the single-shot schedule of Alg. 1, several entries are a multi-shot schedule (every
     decision ranks the rows still active by their Delta_attn in that block), none is the full model. `final`
     [N, d] receives every token's last state. `on_block(l, x_in, idx, n, st, x_out)` is called after every block
@@ -93,7 +93,10 @@ def run_schedule(st: BlockState, x0: torch.Tensor, weights: list, shots: dict, r
     spare = [st.x_a, st.x_b]
     for l, W in enumerate(weights):
         x_out = spare[l & 1]
-        B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, st.q, st.k, st.v, st.h, st.qkv_ws)
+        if "w_qkv" in W:      # one product over the concatenated weight
+            B.dash_rmsnorm_qkv_fused(p, x, W["w_qkv"], n, st.q, st.k, st.v, st.h, st.qkv_ws)
+        else:
+            B.dash_rmsnorm_qkv(p, x, W["w_q"], W["w_k"], W["w_v"], n, st.q, st.k, st.v, st.h, st.qkv_ws)
         if rope_theta is not None:
             B.dash_rope_qk(p, st.q, st.k, idx, n, rope_theta)
         if l in shots:

@@ -220,6 +220,8 @@ def test_multi_shot_schedule_teacher_forced_against_oracle():
         dw = {k: _dev(w[k]) for k in ("w_q", "w_k", "w_v", "w_o", "w_down")}
         dw["w_gate_up"] = B.interleave_gate_up(_dev(w["w_gate"]), _dev(w["w_up"]))
         Wdev.append(dw)
+    for dw in Wdev:                       # front end as one product over [w_q | w_k | w_v]
+        dw["w_qkv"] = B.concat_qkv(dw["w_q"], dw["w_k"], dw["w_v"])
     st = SS.alloc_blocks(d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, m, N)
     st.params.keep_first_n, st.params.keep_last_n = first, last
     lengths = SS.schedule_lengths(N, L, {1: 0.4, 3: 0.5}, first, last)

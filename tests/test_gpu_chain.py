@@ -39,6 +39,18 @@ def test_rmsnorm_qkv_matches_oracle(d):
         assert err.max() <= 2e-2, err.max()
     herr = P.row_rel_err(h.float().cpu().numpy(), ref.rmsnorm(x))
     assert herr.max() <= 8e-3          # one bf16 rounding
+    # the same as one product over [w_q | w_k | w_v] (k and v start inside a 256-column tile when Hq*dh is not a
+    # multiple of 256), without and with scratch for splitting along K
+    wqkv = B.concat_qkv(_dev(W["w_q"]), _dev(W["w_k"]), _dev(W["w_v"]))
+    for ws in (None, torch.empty((max(B.qkv_workspace_bytes(p, n), 256),), dtype=torch.uint8, device="cuda")):
+        q2, k2, v2 = torch.full_like(q, float("nan")), torch.full_like(k, float("nan")), torch.full_like(v, float("nan"))
+        B.dash_rmsnorm_qkv_fused(p, _dev(x), wqkv, n, q2, k2, v2, h, ws)
+        torch.cuda.synchronize()
+        for got, want in ((q2, oq), (k2, ok), (v2, ov)):
+            err = P.row_rel_err(got.float().cpu().numpy().reshape(n, -1), want.reshape(n, -1))
+            assert err.max() <= 2e-2, err.max()
+        if ws is None:                 # same tiles, same order of additions: the same bits as three products
+            assert torch.equal(q2, q) and torch.equal(k2, k) and torch.equal(v2, v)
 
 
 @pytest.mark.parametrize("shape", [(28, 4, 128), (6, 3, 64), (5, 1, 128), (8, 8, 64)], ids=lambda t: "hq%d_hkv%d_dh%d" % t)
@@ -75,6 +87,9 @@ def test_chain_teacher_forced_against_oracle(rope_theta):
     n_layers = 4
     weights_np = [I.make_projection_weights(cfg, l) for l in range(n_layers)]
     weights = [{k: _dev(v) for k, v in W.items()} for W in weights_np]
+    if rope_theta is not None:            # this variant runs the front end as one product over [w_q | w_k | w_v]
+        for W in weights:
+            W["w_qkv"] = B.concat_qkv(W["w_q"], W["w_k"], W["w_v"])
     state = CH.alloc_chain(cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.n)
     x0 = _dev(I.make_hidden(cfg))
     idx0 = torch.from_numpy(I.make_active_idx(cfg.N, cfg.n, cfg.seed)).cuda()
