@@ -117,6 +117,61 @@ def test_ffn_and_front_end_with_few_rows_split_along_k(shape):
         assert P.row_rel_err(_f(got).reshape(n, -1), want_.reshape(n, -1)).max() <= 2e-2
 
 
+def test_seeded_random_shapes_of_the_products_against_oracle():
+    """Sixteen seeded draws of (rows, hidden, heads, head_dim, FFN width) around the tile, half-tile and split
+    boundaries: the front end as three products and as one, the projection with residual and row sums, and the
+    feed-forward, each with scratch for splitting along K, against the oracle."""
+    rng = np.random.default_rng(7)
+    for case in range(16):
+        n = int(rng.choice([1, 2, 31, 64, 65, 127, 128, 129, 177, 255, 256, 257, 300, 511, 513, 700]))
+        dh = int(rng.choice([64, 128]))
+        hkv = int(rng.choice([1, 2, 4]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        d = int(rng.choice([128, 256, 512, 1024, 1536]))
+        m = int(rng.choice([64, 192, 576, 1024]))
+        what = dict(case=case, n=n, d=d, hq=hq, hkv=hkv, dh=dh, m=m)
+        cfg = I.LayerConfig("rnd", "bf16", n, n, d, hq, hkv, dh, 0.3, seed=1000 + case)
+        x = I.make_hidden(cfg)
+        Wp = I.make_projection_weights(cfg, 0)
+        Wf = I.make_ffn_weights(cfg, 0, m)
+        p = P.params_for(cfg)
+        q = torch.empty((n, hq, dh), dtype=torch.bfloat16, device="cuda")
+        k = torch.empty((n, hkv, dh), dtype=torch.bfloat16, device="cuda")
+        v = torch.empty_like(k)
+        h = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+        ws = torch.empty((max(B.qkv_workspace_bytes(p, n), 256),), dtype=torch.uint8, device="cuda")
+        oq, ok, ov = ref.rmsnorm_qkv(x, Wp["w_q"], Wp["w_k"], Wp["w_v"], hq, hkv, dh)
+        for one_product in (False, True):
+            for t in (q, k, v):
+                t.fill_(float("nan"))
+            if one_product:
+                B.dash_rmsnorm_qkv_fused(p, _dev(x), B.concat_qkv(_dev(Wp["w_q"]), _dev(Wp["w_k"]), _dev(Wp["w_v"])), n,
+                                         q, k, v, h, ws)
+            else:
+                B.dash_rmsnorm_qkv(p, _dev(x), _dev(Wp["w_q"]), _dev(Wp["w_k"]), _dev(Wp["w_v"]), n, q, k, v, h, ws)
+            torch.cuda.synchronize()
+            for got, want in ((q, oq), (k, ok), (v, ov)):
+                assert P.row_rel_err(_f(got).reshape(n, -1), want.reshape(n, -1)).max() <= 2e-2, what
+        o = I.round_to_bf16(rng.standard_normal((n, hq * dh)))
+        wsl = torch.empty((B.workspace_bytes(p, n),), dtype=torch.uint8, device="cuda")
+        xn = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+        parts = torch.full((B.norm_partials_per_row(p), n, 2), float("nan"), dtype=torch.float32, device="cuda")
+        B.dash_wo_residual_rownorm(p, _dev(o), _dev(Wp["w_o"]), _dev(x), n, xn, parts, None, wsl)
+        torch.cuda.synchronize()
+        delta = ref.project(o, Wp["w_o"])
+        assert P.row_rel_err(_f(xn), ref.residual(x, delta)).max() <= P.X_TOL["bf16"], what
+        sums = parts.double().sum(dim=0).cpu().numpy()
+        np.testing.assert_allclose(sums[:, 0], (delta ** 2).sum(axis=1), rtol=2e-4, err_msg=str(what))
+        np.testing.assert_allclose(sums[:, 1], (x ** 2).sum(axis=1), rtol=1e-5, err_msg=str(what))
+        out = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+        wsf = torch.empty((B.ffn_workspace_bytes(p, n, m),), dtype=torch.uint8, device="cuda")
+        B.dash_ffn_swiglu(p, _dev(x), B.interleave_gate_up(_dev(Wf["w_gate"]), _dev(Wf["w_up"])), _dev(Wf["w_down"]), n,
+                          m, out, wsf)
+        torch.cuda.synchronize()
+        want = ref.ffn_swiglu(x, Wf["w_gate"], Wf["w_up"], Wf["w_down"])
+        assert P.row_rel_err(_f(out), want).max() <= P.X_TOL["bf16"], what
+
+
 def test_scatter_rows_matches_oracle():
     n, d, N = 333, 256, 1000
     rng = np.random.default_rng(60)
