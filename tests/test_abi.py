@@ -71,3 +71,29 @@ def test_schedule_host_helpers_agree_with_the_oracle():
             assert SS.schedule_lengths(n, L, shots, 64, 32) == ref.schedule_lengths(n, L, shots, 64, 32)
     with pytest.raises(ValueError):
         SS.comparable_multi_shot_ratio(1000, 4, [1], 0.0, 64, 128)
+
+
+def test_workspace_sizes_grow_with_capacity_and_hold_the_split_sums():
+    """Host arithmetic of the workspace sizes: monotone in the capacity, and with room for at least two fp32
+    [n, N] split sums wherever a product of n rows fills at most half of 256 compute units with its tiles."""
+    p = B.make_params(3584, 28, 4, 128)
+    prev = (0, 0, 0)
+    for n in (0, 1, 64, 177, 256, 1000, 2304, 4096, 16384, 32768):
+        cur = (B.workspace_bytes(p, n), B.ffn_workspace_bytes(p, n, 18944), B.qkv_workspace_bytes(p, n))
+        assert all(c >= q for c, q in zip(cur, prev)), (n, cur, prev)
+        prev = cur
+    # 177 rows: the projection has 14 tiles, the q/k/v product 18, the FFN down projection 14
+    assert B.workspace_bytes(p, 177) >= 2 * 177 * 3584 * 4
+    assert B.qkv_workspace_bytes(p, 177) >= 2 * 177 * 4608 * 4
+    assert B.ffn_workspace_bytes(p, 177, 18944) >= 177 * (3584 + 18944) * 2 + 2 * 177 * 3584 * 4
+    # a capacity whose tiles fill the chip needs no room for split sums
+    big = B.workspace_bytes(p, 32768)
+    assert big < 32768 * 3584 * 2 + 32768 * 56 * 8 + (80 << 20)
+    assert B.qkv_workspace_bytes(B.make_params(3584, 28, 4, 128, dtype=B.DASH_F32), 177) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
