@@ -242,3 +242,37 @@ def test_invalid_arguments_are_rejected_without_launch():
     mis = D["x"].view(-1)[1:1 + (cfg.n - 1) * cfg.d].view(cfg.n - 1, cfg.d)   # 2-byte offset
     with pytest.raises(B.DashError, match="invalid"):
         B.dash_attn_layer(params, mis, D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], cfg.n - 1, buf)
+
+
+@pytest.mark.parametrize("slope", [0.0, 8.0, 40.0, -40.0], ids=lambda s: "slope%g" % s)
+@pytest.mark.parametrize("dh", [64, 128])
+def test_flash_softmax_reference_moves_with_the_scores(dh, slope):
+    """Scores that drift along the key axis by `slope` (natural-log units) per 64-key tile, up to hundreds over
+    the sequence: the kernel's softmax reference is not the running maximum and moves only when a row sum leaves
+    a modest range, so drifting scores exercise every branch of it (move at nearly every tile when they rise
+    steeply, never after the first tile when they fall, underflow of everything but the newest keys). The
+    attention output against the oracle on the same bf16 inputs."""
+    import torch
+    n, hq, hkv = 777, 4, 2
+    rng = np.random.default_rng(400 + dh + int(slope))
+    u = rng.standard_normal(dh)
+    u /= np.linalg.norm(u)
+    ramp = (np.arange(n) / 64.0) * slope                          # target drift of the logit along the keys
+    q = rng.standard_normal((n, hq, dh)) * 0.5 + 4.0 * u          # q . u = 4 (+ noise)
+    k = rng.standard_normal((n, hkv, dh)) * 0.5 + (ramp * np.sqrt(dh) / 4.0)[:, None, None] * u
+    v = rng.standard_normal((n, hkv, dh))
+    q, k, v = I.round_to_bf16(q), I.round_to_bf16(k), I.round_to_bf16(v)
+    pos = np.arange(n, dtype=np.int32)
+    p = B.make_params(hq * dh, hq, hkv, dh, causal=True)
+    for causal in (True, False):
+        p.causal = int(causal)
+        o = torch.empty((n, hq * dh), dtype=torch.bfloat16, device="cuda")
+        B.dash_flash_fwd(p, B.to_device(q, B.DASH_BF16), B.to_device(k, B.DASH_BF16), B.to_device(v, B.DASH_BF16),
+                         torch.from_numpy(pos).cuda(), n, o)
+        torch.cuda.synchronize()
+        want = ref.attention_rows(q, k, v, pos, causal=causal)
+        got = o.float().cpu().numpy()
+        assert np.isfinite(got).all()
+        err = P.row_rel_err(got, want)
+        print("drift", dh, slope, causal, float(err.max()))
+        assert err.max() <= P.X_TOL["bf16"], (causal, float(err.max()))
