@@ -217,13 +217,17 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
     const uint32_t lds_a = lds0 + (uint32_t)(wave * ADMA * 1024);
     const uint32_t lds_b = lds0 + (uint32_t)(kGAElems * 2 + wave * BDMA * 1024);
-    auto dma_next_step = [&](int stage) {  // K steps are fetched strictly in order
+    // K steps are fetched strictly in order; the A and the B tile of a step are requested separately
+    auto dma_next_a = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
         for (int i = 0; i < ADMA; ++i) {
             gemm_dma_load16(a_ptr[i], lds_a + so + i * 1024);
             a_ptr[i] += kGK * sizeof(__bf16);
         }
+    };
+    auto dma_next_b = [&](int stage) {
+        const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
         for (int i = 0; i < BDMA; ++i) {
             gemm_dma_load16(b_ptr[i], lds_b + so + i * 1024);
@@ -281,9 +285,11 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         }
     };
     constexpr int kStepLoads = ADMA + BDMA;
-    dma_next_step(0);
+    dma_next_a(0);
+    dma_next_b(0);
     if (n_ksteps > 1) {
-        dma_next_step(1);
+        dma_next_a(1);
+        dma_next_b(1);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepLoads) : "memory");  // step 0 has landed, step 1 may be in flight
     } else {
         gemm_dma_wait();
@@ -294,9 +300,14 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     // slice before it run, across the step boundary too: the wait for the next step's tiles and the barrier
     // that publishes them sit before the last slice's MFMAs, whose fragments are in registers by then, and
     // the first slice of the next step is read from the other stage while those MFMAs run. After that
-    // barrier every wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it.
+    // barrier every wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it:
+    // the A tile right there, the B tile a slice later at the top of the next round. A wave's load
+    // instructions queue behind everybody else's in the one address unit of the compute unit, and a wave that
+    // cannot issue its next load cannot issue its MFMAs either; two short bursts stall the matrix pipe less
+    // than one long one (8 % at the full clock), and both still leave the loads most of a step to land.
     for (int kt = 0; kt < n_ksteps; ++kt) {
         const int st = kt & 1;
+        if (kt >= 1 && kt + 1 < n_ksteps) dma_next_b(st ^ 1);  // B tile of step kt + 1 (its A tile is on its way)
 #pragma unroll
         for (int ks = 0; ks < 3; ++ks) {
             read_frags(st, ks + 1, Af[(ks + 1) & 1], Bf[(ks + 1) & 1]);
@@ -307,7 +318,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         gemm_dma_wait();
         asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the last slice's fragments are in registers
         lds_barrier();
-        if (kt + 2 < n_ksteps) dma_next_step(st);
+        if (kt + 2 < n_ksteps) dma_next_a(st);
         read_frags(st ^ 1, 0, Af[0], Bf[0]);  // after the last step: stale data, never used
         mfma_slice(Af[1], Bf[1]);
         pin_slice();
