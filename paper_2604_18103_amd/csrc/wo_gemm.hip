@@ -96,14 +96,17 @@ __global__ __launch_bounds__(256) void wo_simple_kernel(const T* __restrict__ A,
 
 // ------------------------------------------------------------------------------------------------
 // MFMA kernel (bf16): C[M,N] = A[M,K] B[K,N], A and B row-major.
-// Workgroup tile 256x256, K step 64; 8 waves in 2 (M) x 4 (N), two per SIMD, each wave 128x64 = 4x2 MFMA
-// 32x32x16 blocks (128 fp32 accumulator registers per lane). A fragments are 16-byte LDS reads from the
-// [m][k] tile; B fragments come from the natural [k][n] tile through LDS transpose reads.
+// Workgroup tile 256x256, K step 64; 8 waves in 2 (M) x 4 (N), two per SIMD, each wave 128x64 = 8x4 blocks of
+// v_mfma_f32_16x16x32_bf16 (128 fp32 accumulator registers per lane). On normally distributed operands the part
+// is power-limited, and this shape moves fewer accumulator registers per flop than 32x32x16: the same tiles and
+// LDS traffic finish 1-2 % sooner end to end, although twice the MFMA instructions cost cycles at the full
+// clock. A fragments are 16-byte LDS reads from the [m][k] tile; B fragments come from the natural [k][n] tile
+// through LDS transpose reads.
 // The tiles of a K step go from global memory straight into LDS (no registers in between). Such a load
 // writes 1 KB of consecutive LDS per wave instruction, so rows cannot be padded; bank conflicts are avoided
 // by an XOR swizzle of the 16-byte chunk index inside a row: A (128-byte rows, 16-byte reads of one chunk
-// from 16 consecutive rows) by (row / 2) % 8, B (512-byte rows, transpose reads of 4 rows x 4 chunks per 32
-// lanes) by 4 * (row % 4).
+// from 16 consecutive rows) by (row / 2) % 8, B (512-byte rows; 32 lanes read 4 k-rows and the 4 k-rows 8
+// below them, 32 bytes of each) by 4 * (row % 4) + 2 * ((row / 8) % 2).
 // ------------------------------------------------------------------------------------------------
 constexpr int kGM = 256, kGN = 256, kGK = 64;
 constexpr int kGThreads = 512;
@@ -182,13 +185,14 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     const int tile_m = tile % n_mtiles, tile_n = tile / n_mtiles;
     const int m0 = tile_m * kGM + (MB == 4 ? 0 : ((int)blockIdx.x % 2) * BM), n0 = tile_n * kGN;
 
-    f32x16 acc[MB][2];
+    constexpr int RB = 2 * MB;  // 16-row blocks of the wave's tile; 4 column blocks of 16
+    f32x4 acc[RB][4];
 #pragma unroll
-    for (int a = 0; a < MB; ++a)
+    for (int a = 0; a < RB; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+            for (int r = 0; r < 4; ++r) acc[a][b][r] = 0.f;
 
     // K steps of this workgroup: all of them, or those of split blockIdx.y
     const int ks0 = (int)blockIdx.y * ksteps_per_split;
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
 #pragma unroll
     for (int i = 0; i < BDMA; ++i) {
         const int row = (wave * BDMA + i) * 2 + lane / 32;
-        const int lchunk = (lane % 32) ^ (4 * (row % 4));
+        const int lchunk = (lane % 32) ^ (4 * (row % 4) + 2 * ((row / 8) % 2));
         b_ptr[i] = reinterpret_cast<const char*>(B + (size_t)(ks0 * kGK + row) * N + min(n0 + lchunk * 8, N - 8));
     }
     const size_t b_step = (size_t)kGK * N * sizeof(__bf16);
@@ -242,45 +246,48 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
     };
-    // Fragments of one 16-wide slice: MB A fragments (16-byte reads) and two B fragments (transpose reads).
-    bf16x8 Af[2][MB], Bf[2][2];
+    // Fragments of one 32-wide slice for v_mfma_f32_16x16x32_bf16: RB A fragments (rows 16 rb + i, k-slots
+    // 8 g .. 8 g + 7: one 16-byte read) and four B fragments (columns 16 cb + i, the same k-slots: two transpose
+    // reads of a 4 x 16 block each), lane = 16 g + i.
+    const int fi = lane % 16, fg = lane / 16;
+    bf16x8 Af[2][RB], Bf[2][4];
     auto read_frags = [&](int st, int ks, bf16x8* af, bf16x8* bfr) {
         const __bf16* sa = smem + st * kGStageElems;
         const __bf16* sb = sa + kGAElems;
+        // B first: the MFMAs of a slice go through the row blocks in order and need every B fragment at once
 #pragma unroll
-        for (int a = 0; a < MB; ++a) {
-            const int row = wm * WM + 32 * a + j;
-            af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((2 * ks + h) ^ ((row / 2) % 8)) * 8]);
-        }
-#pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            // lane (tg, ti): rows k = 16ks + 8*(tg/2) + ti/4 (+4), columns wn*64 + 32b + 16*(tg%2) + 4*(ti%4)
-            const int krow = 16 * ks + 8 * (tg / 2) + ti / 4;
-            const int col = wn * 64 + 32 * b + 16 * (tg % 2) + 4 * (ti % 4);
-            const int scol = ((col / 8) ^ (4 * (krow % 4))) * 8 + col % 8;  // krow + 4 swizzles alike
+        for (int b = 0; b < 4; ++b) {
+            const int krow = 32 * ks + 8 * fg + fi / 4;  // and krow + 4: the same swizzle
+            const int col = wn * 64 + 16 * b + 4 * (fi % 4);
+            const int scol = ((col / 8) ^ (4 * (krow % 4) + 2 * ((krow / 8) % 2))) * 8 + col % 8;
             const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
             const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
             bfr[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
+#pragma unroll
+        for (int a = 0; a < RB; ++a) {
+            const int row = wm * WM + 16 * a + fi;
+            af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((4 * ks + fg) ^ ((row / 2) % 8)) * 8]);
+        }
     };
     auto mfma_slice = [&](const bf16x8* af, const bf16x8* bfr) {
 #pragma unroll
-        for (int a = 0; a < MB; ++a)
+        for (int a = 0; a < RB; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
+            for (int b = 0; b < 4; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[a], bfr[b], acc[a][b], 0, 0, 0);
     };
-    // issue order of one slice: every MFMA paired with fragment reads of the slice after it
-    constexpr int RD = MB + 4, MF = 2 * MB;  // LDS reads and MFMAs per slice: 8 and 8, or 6 and 4
+    // issue order of one slice: the fragment reads of the slice after it spread between its MFMAs
+    constexpr int RD = RB + 8, MF = 4 * RB;  // LDS reads and MFMAs per slice: 16 and 32, or 12 and 16
     auto pin_slice = [] {
 #pragma unroll
-        for (int i = 0; i < RD - MF; ++i) {  // half tiles: two reads behind each of the first two MFMAs
+        for (int i = 0; i < 2 * RD - MF; ++i) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
 #pragma unroll
-        for (int i = 0; i < 2 * MF - RD; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        for (int i = 0; i < MF - RD; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
@@ -296,29 +303,23 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     }
     __syncthreads();
     read_frags(0, 0, Af[0], Bf[0]);
-    // One round per K step of four 16-wide slices. The fragments of a slice are read while the MFMAs of the
-    // slice before it run, across the step boundary too: the wait for the next step's tiles and the barrier
-    // that publishes them sit before the last slice's MFMAs, whose fragments are in registers by then, and
-    // the first slice of the next step is read from the other stage while those MFMAs run. After that
-    // barrier every wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it:
-    // the A tile right there, the B tile a slice later at the top of the next round. A wave's load
-    // instructions queue behind everybody else's in the one address unit of the compute unit, and a wave that
-    // cannot issue its next load cannot issue its MFMAs either; two short bursts stall the matrix pipe less
-    // than one long one (8 % at the full clock), and both still leave the loads most of a step to land.
+    // One round per K step of two 32-wide slices. The fragments of a slice are read while the MFMAs of the slice
+    // before it run, across the step boundary too: the wait for the next step's tiles and the barrier that
+    // publishes them sit before the second slice's MFMAs, whose fragments are in registers by then, and the
+    // first slice of the next step is read from the other stage while those MFMAs run. After that barrier every
+    // wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it.
     for (int kt = 0; kt < n_ksteps; ++kt) {
         const int st = kt & 1;
-        if (kt >= 1 && kt + 1 < n_ksteps) dma_next_b(st ^ 1);  // B tile of step kt + 1 (its A tile is on its way)
-#pragma unroll
-        for (int ks = 0; ks < 3; ++ks) {
-            read_frags(st, ks + 1, Af[(ks + 1) & 1], Bf[(ks + 1) & 1]);
-            mfma_slice(Af[ks & 1], Bf[ks & 1]);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 3; ++ks) pin_slice();
+        read_frags(st, 1, Af[1], Bf[1]);
+        mfma_slice(Af[0], Bf[0]);
+        pin_slice();
         gemm_dma_wait();
-        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the last slice's fragments are in registers
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the second slice's fragments are in registers
         lds_barrier();
-        if (kt + 2 < n_ksteps) dma_next_a(st);
+        if (kt + 2 < n_ksteps) {
+            dma_next_a(st);
+            dma_next_b(st);
+        }
         read_frags(st ^ 1, 0, Af[0], Bf[0]);  // after the last step: stale data, never used
         mfma_slice(Af[1], Bf[1]);
         pin_slice();
@@ -346,10 +347,12 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     for (int a = 0; a < MB; ++a) {
         if (EPI == EPI_RESIDUAL_NORM && a + 1 < MB) fetch_x(a + 1, xv[(a + 1) & 1]);
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r)  // accumulator register r: local row 8*(r/4) + 4h + r%4, column j
-                stage[(8 * (r / 4) + 4 * h + r % 4) * kEpiStr + 32 * b + j] = acc[a][b][r];
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)  // accumulator register r of a 16x16 block: row 4 g + r, column i
+                    stage[(16 * sb + 4 * fg + r) * kEpiStr + 16 * b + fi] = acc[2 * a + sb][b][r];
         __syncthreads();  // every wave runs the same epilogue schedule, so the barrier is uniform
         if (EPI == EPI_SWIGLU) {
             // 4 lanes per row: lane c takes gate columns 8c..8c+7 and the up columns 32 + 8c..
