@@ -178,7 +178,6 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     __bf16* smem = reinterpret_cast<__bf16*>(gemm_smem_raw);
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int j = lane % 32, h = lane / 32;
     const int wm = wave / 4, wn = wave % 4;
     // consecutive workgroups walk down M inside one column tile, so the B panel stays hot in L2
     const int tile = first_tile + (MB == 4 ? (int)blockIdx.x : (int)blockIdx.x / 2);
@@ -239,7 +238,6 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         }
     };
 
-    const int tg = lane / 16, ti = lane % 16;
     // barrier that orders LDS traffic only
     auto lds_barrier = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
