@@ -161,14 +161,15 @@ struct FaSmem {
     __device__ static constexpr int v_swz(int row) { return 4 * ((row / RP) % (CPR / 4)); }
 };
 
-// One direct global->LDS load: lane l's 16 bytes at `gptr` land at LDS address lds_base + 16*l. Issued as
-// inline asm so that the compiler's wait-count bookkeeping does not tie every later LDS read to it; the
-// kernel waits for these loads explicitly (dma_wait) before the barrier that publishes a stage.
-// (M0 holds the LDS base; naming it as a clobber is what keeps the compiler from caching a value in it.)
+// One direct global->LDS load: lane l's 16 bytes at `base + voff` (uniform base, per-lane 32-bit offset) land at
+// LDS address lds_base + 16*l. Issued as inline asm so that the compiler's wait-count bookkeeping does not tie
+// every later LDS read to it; the kernel waits for these loads explicitly (dma_wait) before the barrier that
+// publishes a stage. (M0 holds the LDS base; naming it as a clobber is what keeps the compiler from caching a
+// value in it.)
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma_load16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+__device__ __forceinline__ void dma_load16(const void* base, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(base) : "memory", "m0");
 }
 #pragma clang diagnostic pop
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
@@ -246,32 +247,41 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     // Staging by direct global->LDS loads, no registers in between: the four waves of group 0 fetch the K
     // tiles, those of group 1 the V tiles. One wave instruction moves 1 KB = ROWS_PER_DMA rows; lane l
     // lands in physical chunk l % CPR of row l / CPR, so it fetches the logical chunk that the swizzle maps
-    // there. 32-bit byte offsets (the launcher checks the tensors are below 2 GiB), advanced by one tile per
-    // load and clamped to the last row.
+    // there. The address of a load is a scalar tile base (advanced by scalar arithmetic) plus a 32-bit lane offset
+    // that is the same for every whole tile (the launcher checks the tensors are below 2 GiB); only the last,
+    // partly filled tile recomputes the offsets, with rows beyond the end clamped to the last row.
     constexpr int ROWS_PER_DMA = 64 / SM::CPR;                  // 4 (DH 128) or 8 (DH 64)
     constexpr int DMAS = kFaBN / ROWS_PER_DMA / 4;              // per wave and tile: 4 or 2
     const int gw = wave & 3;                                    // wave inside its group
     const uint32_t row_bytes = (uint32_t)Hkv * DH * 2u;
-    const uint32_t last_row_off = (uint32_t)(n - 1) * row_bytes;
     const uint32_t tile_bytes = (uint32_t)kFaBN * row_bytes;
-    uint32_t dma_off[DMAS];   // byte offset of this lane's row in the current tile (clamped)
-    uint32_t dma_col[DMAS];   // byte offset of this lane's logical chunk inside the row
+    const int dma_row0 = gw * DMAS * ROWS_PER_DMA + lane / SM::CPR;  // this lane's row in the tile for load 0
+    uint32_t dma_voff[DMAS];   // byte offset of this lane's 16 bytes from the start of a whole tile
 #pragma unroll
     for (int i = 0; i < DMAS; ++i) {
-        const int r = (gw * DMAS + i) * ROWS_PER_DMA + lane / SM::CPR;  // row in the tile
+        const int r = dma_row0 + i * ROWS_PER_DMA;
         const int pchunk = lane % SM::CPR;
         const int lchunk = pchunk ^ (grp == 0 ? SM::k_swz(r) : SM::v_swz(r));
-        dma_off[i] = min((uint32_t)r * row_bytes, last_row_off);
-        dma_col[i] = ((uint32_t)g * DH + lchunk * 8) * 2u;
+        dma_voff[i] = (uint32_t)r * row_bytes + ((uint32_t)g * DH + lchunk * 8) * 2u;
     }
     const char* dma_base = reinterpret_cast<const char*>(grp == 0 ? k : v);
     const uint32_t lds_stage0 = lds_addr(grp == 0 ? Kst : Vst) + (uint32_t)(gw * DMAS * 1024);
-    auto dma_next_tile = [&](int stage) {  // tiles are fetched strictly in order: 0, 1, 2, ...
+    int dma_tile = 0;  // tiles are fetched strictly in order: 0, 1, 2, ...
+    auto dma_next_tile = [&](int stage) {
+        const char* tile_base = dma_base + (size_t)dma_tile * tile_bytes;
+        const int rows_left = n - dma_tile * kFaBN;  // >= 1: only tiles that hold a row are fetched
+        ++dma_tile;
+        if (rows_left >= kFaBN) {
 #pragma unroll
-        for (int i = 0; i < DMAS; ++i) {
-            dma_load16(dma_base + dma_off[i] + dma_col[i],
-                       lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
-            dma_off[i] = min(dma_off[i] + tile_bytes, last_row_off);
+            for (int i = 0; i < DMAS; ++i)
+                dma_load16(tile_base, dma_voff[i], lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
+        } else {
+#pragma unroll
+            for (int i = 0; i < DMAS; ++i) {
+                const int beyond = max(dma_row0 + i * ROWS_PER_DMA - (rows_left - 1), 0);  // rows past the last one
+                dma_load16(tile_base, dma_voff[i] - (uint32_t)beyond * row_bytes,
+                           lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
+            }
         }
     };
 
@@ -314,7 +324,12 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
         }
         __builtin_amdgcn_sched_group_barrier(0x008, DB, 0);
     };
-    // S^T = K(t) Q^T
+    // S^T = K(t) Q^T. A fragment: key row 32 kb + j, chunk 2 kc + h; rows j and 32 + j swizzle alike, so the key
+    // block only adds a constant to the element offset k_elem[kc].
+    static_assert((32 / SM::RP) % SM::CPR == 0, "rows j and j + 32 must share the K swizzle");
+    int k_elem[KC];
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) k_elem[kc] = j * DH + ((2 * kc + h) ^ SM::k_swz(j)) * 8;
     auto qk_mfma = [&](int t) {
         const __bf16* Ks = Kst + (t & 1) * SM::STAGE_ELEMS;
 #pragma unroll
@@ -323,8 +338,7 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
             for (int r = 0; r < 16; ++r) S[kb][r] = Cneg[r];
 #pragma unroll
             for (int kc = 0; kc < KC; ++kc) {
-                const int krow = 32 * kb + j;
-                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[krow * DH + ((2 * kc + h) ^ SM::k_swz(krow)) * 8]);
+                const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[k_elem[kc] + 32 * kb * DH]);
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
             }
         }
