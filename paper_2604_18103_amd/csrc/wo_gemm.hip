@@ -123,14 +123,14 @@ __device__ __forceinline__ s16x4 lds_read_tr16_b(const __bf16* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
 }
 
-// One direct global->LDS load: lane l's 16 bytes at `gptr` land at LDS address lds_base + 16*l. Inline asm,
-// so the compiler's wait-count bookkeeping does not tie every later LDS read to it; the kernel waits for
-// these loads explicitly before the barrier that publishes a stage. (M0 holds the LDS base; naming it as a
-// clobber is what keeps the compiler from caching a value in it.)
+// One direct global->LDS load: lane l's 16 bytes at `base + voff` (uniform base, per-lane 32-bit offset) land at
+// LDS address lds_base + 16*l. Inline asm, so the compiler's wait-count bookkeeping does not tie every later LDS
+// read to it; the kernel waits for these loads explicitly before the barrier that publishes a stage. (M0 holds
+// the LDS base; naming it as a clobber is what keeps the compiler from caching a value in it.)
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void gemm_dma_load16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_base), "v"(gptr) : "memory", "m0");
+__device__ __forceinline__ void gemm_dma_load16(const void* base, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(base) : "memory", "m0");
 }
 #pragma clang diagnostic pop
 __device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
@@ -201,21 +201,25 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     // one instruction = 2 rows. Lane l lands in physical chunk l % (chunks per row) of its row and therefore
     // fetches the logical chunk that the swizzle maps there. Rows beyond M and columns beyond N are clamped:
     // they are computed on valid data and never stored.
+    // The address of a load is a scalar base (this workgroup's tile at the current K step, advanced by scalar
+    // arithmetic) plus a 32-bit lane offset that never changes.
     constexpr int ADMA = BM / 8 / 8, BDMA = kGK / 2 / 8;  // load instructions per wave and K step
-    const char* a_ptr[ADMA];
-    const char* b_ptr[BDMA];
+    uint32_t a_off[ADMA], b_off[BDMA];
+    const int m0c = min(m0, M - 1);  // the second half tile of a last row tile may lie wholly beyond M
 #pragma unroll
     for (int i = 0; i < ADMA; ++i) {
         const int row = (wave * ADMA + i) * 8 + lane / 8;
         const int lchunk = (lane % 8) ^ ((row / 2) % 8);
-        a_ptr[i] = reinterpret_cast<const char*>(A + (size_t)min(m0 + row, M - 1) * K + ks0 * kGK + lchunk * 8);
+        a_off[i] = (uint32_t)(((size_t)(min(m0 + row, M - 1) - m0c) * K + lchunk * 8) * sizeof(__bf16));
     }
 #pragma unroll
     for (int i = 0; i < BDMA; ++i) {
         const int row = (wave * BDMA + i) * 2 + lane / 32;
         const int lchunk = (lane % 32) ^ (4 * (row % 4) + 2 * ((row / 8) % 2));
-        b_ptr[i] = reinterpret_cast<const char*>(B + (size_t)(ks0 * kGK + row) * N + min(n0 + lchunk * 8, N - 8));
+        b_off[i] = (uint32_t)(((size_t)row * N + (min(n0 + lchunk * 8, N - 8) - n0)) * sizeof(__bf16));
     }
+    const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0c * K + (size_t)ks0 * kGK);
+    const char* b_base = reinterpret_cast<const char*>(B + (size_t)ks0 * kGK * N + n0);
     const size_t b_step = (size_t)kGK * N * sizeof(__bf16);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
     const uint32_t lds_a = lds0 + (uint32_t)(wave * ADMA * 1024);
@@ -224,18 +228,14 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     auto dma_next_a = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
-        for (int i = 0; i < ADMA; ++i) {
-            gemm_dma_load16(a_ptr[i], lds_a + so + i * 1024);
-            a_ptr[i] += kGK * sizeof(__bf16);
-        }
+        for (int i = 0; i < ADMA; ++i) gemm_dma_load16(a_base, a_off[i], lds_a + so + i * 1024);
+        a_base += kGK * sizeof(__bf16);
     };
     auto dma_next_b = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
-        for (int i = 0; i < BDMA; ++i) {
-            gemm_dma_load16(b_ptr[i], lds_b + so + i * 1024);
-            b_ptr[i] += b_step;
-        }
+        for (int i = 0; i < BDMA; ++i) gemm_dma_load16(b_base, b_off[i], lds_b + so + i * 1024);
+        b_base += b_step;
     };
 
     // barrier that orders LDS traffic only
