@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdash.so")
+CHECK_LIB = os.path.join(HERE, "libdash_staging_check.so")  # host-only: CPU check of the kernels' staging addresses
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "flash_fwd.hip", "wo_gemm.hip", "rope.hip", "score_decide.hip", "compact.hip"]
 
@@ -49,7 +50,20 @@ def build_lib(extra_flags: list[str] | None = None) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}{r.stderr}")
+    build_staging_check()
     return LIB
+
+
+def build_staging_check() -> str:
+    """Compile the host-side address checker (plain C++, no GPU code) with the system compiler."""
+    cmd = [os.environ.get("CXX", "g++"), "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", f"-I{CSRC}",
+           os.path.join(CSRC, "staging_check.cpp"), "-o", CHECK_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"g++ failed for staging_check.cpp:\n{r.stdout}{r.stderr}")
+    if (r.stdout + r.stderr).strip():
+        print(r.stdout + r.stderr, file=sys.stderr)
+    return CHECK_LIB
 
 
 if __name__ == "__main__":

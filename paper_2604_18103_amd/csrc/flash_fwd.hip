@@ -10,6 +10,7 @@
 //   flash_fwd_mfma<DH>  bf16, MFMA 32x32x16, fp32 softmax and accumulation (the hot kernel)
 //   flash_fwd_simple<T> one wave per (row, head), plain FMA; the fp32 path
 #include "common.h"
+#include "staging_addr.h"
 
 namespace dash {
 
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, 
 // B holds column i, k-slots 8h..8h+7; D register r holds row 8*(r/4) + 4h + r%4 of column i.
 // ------------------------------------------------------------------------------------------------
 constexpr int kFaBM = 256;  // query rows per workgroup
-constexpr int kFaBN = 64;   // keys per tile
+// keys per tile: kFaBN = 64 (staging_addr.h)
 constexpr int kFaThreads = 512;
 constexpr float kMaskedScore = -1.0e30f;
 constexpr float kRowSumLimit = 1048576.0f;  // a lane's 32-key partial row sum above this moves the softmax reference
@@ -157,8 +158,8 @@ struct FaSmem {
     static constexpr int RP = 256 / (DH * 2);      // rows per 256 bytes of LDS (one pass over all banks)
     static constexpr int STAGE_ELEMS = kFaBN * DH;
     static constexpr size_t BYTES = 5 * STAGE_ELEMS * sizeof(__bf16);  // two stages of K, three of V
-    __device__ static constexpr int k_swz(int row) { return (row / RP) % CPR; }
-    __device__ static constexpr int v_swz(int row) { return 4 * ((row / RP) % (CPR / 4)); }
+    __device__ static constexpr int k_swz(int row) { return fa_k_swz(row, DH); }
+    __device__ static constexpr int v_swz(int row) { return fa_v_swz(row, DH); }
 };
 
 // One direct global->LDS load: lane l's 16 bytes at `base + voff` (uniform base, per-lane 32-bit offset) land at
@@ -250,20 +251,12 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     // there. The address of a load is a scalar tile base (advanced by scalar arithmetic) plus a 32-bit lane offset
     // that is the same for every whole tile (the launcher checks the tensors are below 2 GiB); only the last,
     // partly filled tile recomputes the offsets, with rows beyond the end clamped to the last row.
-    constexpr int ROWS_PER_DMA = 64 / SM::CPR;                  // 4 (DH 128) or 8 (DH 64)
-    constexpr int DMAS = kFaBN / ROWS_PER_DMA / 4;              // per wave and tile: 4 or 2
+    constexpr int DMAS = fa_dmas(DH);                           // loads per wave and tile: 4 (DH 128) or 2 (DH 64)
     const int gw = wave & 3;                                    // wave inside its group
-    const uint32_t row_bytes = (uint32_t)Hkv * DH * 2u;
-    const uint32_t tile_bytes = (uint32_t)kFaBN * row_bytes;
-    const int dma_row0 = gw * DMAS * ROWS_PER_DMA + lane / SM::CPR;  // this lane's row in the tile for load 0
+    const uint32_t tile_bytes = (uint32_t)fa_tile_bytes(Hkv, DH);
     uint32_t dma_voff[DMAS];   // byte offset of this lane's 16 bytes from the start of a whole tile
 #pragma unroll
-    for (int i = 0; i < DMAS; ++i) {
-        const int r = dma_row0 + i * ROWS_PER_DMA;
-        const int pchunk = lane % SM::CPR;
-        const int lchunk = pchunk ^ (grp == 0 ? SM::k_swz(r) : SM::v_swz(r));
-        dma_voff[i] = (uint32_t)r * row_bytes + ((uint32_t)g * DH + lchunk * 8) * 2u;
-    }
+    for (int i = 0; i < DMAS; ++i) dma_voff[i] = fa_dma_voff(fa_dma_row(gw, i, lane, DH), lane, g, Hkv, DH, grp == 0);
     const char* dma_base = reinterpret_cast<const char*>(grp == 0 ? k : v);
     const uint32_t lds_stage0 = lds_addr(grp == 0 ? Kst : Vst) + (uint32_t)(gw * DMAS * 1024);
     int dma_tile = 0;  // tiles are fetched strictly in order: 0, 1, 2, ...
@@ -277,11 +270,9 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
                 dma_load16(tile_base, dma_voff[i], lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
         } else {
 #pragma unroll
-            for (int i = 0; i < DMAS; ++i) {
-                const int beyond = max(dma_row0 + i * ROWS_PER_DMA - (rows_left - 1), 0);  // rows past the last one
-                dma_load16(tile_base, dma_voff[i] - (uint32_t)beyond * row_bytes,
+            for (int i = 0; i < DMAS; ++i)
+                dma_load16(tile_base, fa_dma_voff_tail(dma_voff[i], fa_dma_row(gw, i, lane, DH), rows_left, Hkv, DH),
                            lds_stage0 + (uint32_t)(stage * SM::STAGE_ELEMS * 2 + i * 1024));
-            }
         }
     };
 

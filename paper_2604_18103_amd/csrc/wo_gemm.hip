@@ -10,6 +10,7 @@
 //
 // norm_partials layout: [P][n][2] fp32, P = column tiles (x wave columns) of the kernel in use.
 #include "common.h"
+#include "staging_addr.h"
 
 namespace dash {
 
@@ -108,8 +109,7 @@ __global__ __launch_bounds__(256) void wo_simple_kernel(const T* __restrict__ A,
 // from 16 consecutive rows) by (row / 2) % 8, B (512-byte rows; 32 lanes read 4 k-rows and the 4 k-rows 8
 // below them, 32 bytes of each) by 4 * (row % 4) + 2 * ((row / 8) % 2).
 // ------------------------------------------------------------------------------------------------
-constexpr int kGM = 256, kGN = 256, kGK = 64;
-constexpr int kGThreads = 512;
+constexpr int kGThreads = kGWaves * kWave;  // tile constants kGM, kGN, kGK: staging_addr.h
 constexpr int kGAElems = kGM * kGK, kGBElems = kGK * kGN;
 constexpr int kGStageElems = kGAElems + kGBElems;
 constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (131072 B)
@@ -203,24 +203,21 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     // they are computed on valid data and never stored.
     // The address of a load is a scalar base (this workgroup's tile at the current K step, advanced by scalar
     // arithmetic) plus a 32-bit lane offset that never changes.
-    constexpr int ADMA = BM / 8 / 8, BDMA = kGK / 2 / 8;  // load instructions per wave and K step
+    constexpr int ADMA = gemm_adma(BM), BDMA = gemm_bdma();  // load instructions per wave and K step
     uint32_t a_off[ADMA], b_off[BDMA];
-    const int m0c = min(m0, M - 1);  // the second half tile of a last row tile may lie wholly beyond M
 #pragma unroll
     for (int i = 0; i < ADMA; ++i) {
-        const int row = (wave * ADMA + i) * 8 + lane / 8;
-        const int lchunk = (lane % 8) ^ ((row / 2) % 8);
-        a_off[i] = (uint32_t)(((size_t)(min(m0 + row, M - 1) - m0c) * K + lchunk * 8) * sizeof(__bf16));
+        const int row = gemm_a_row(wave, i, lane, ADMA);
+        a_off[i] = gemm_a_off(m0, M, K, row, gemm_a_lchunk(row, lane));
     }
 #pragma unroll
     for (int i = 0; i < BDMA; ++i) {
-        const int row = (wave * BDMA + i) * 2 + lane / 32;
-        const int lchunk = (lane % 32) ^ (4 * (row % 4) + 2 * ((row / 8) % 2));
-        b_off[i] = (uint32_t)(((size_t)row * N + (min(n0 + lchunk * 8, N - 8) - n0)) * sizeof(__bf16));
+        const int row = gemm_b_row(wave, i, lane);
+        b_off[i] = gemm_b_off(n0, N, row, gemm_b_lchunk(row, lane));
     }
-    const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0c * K + (size_t)ks0 * kGK);
-    const char* b_base = reinterpret_cast<const char*>(B + (size_t)ks0 * kGK * N + n0);
-    const size_t b_step = (size_t)kGK * N * sizeof(__bf16);
+    const char* a_base = reinterpret_cast<const char*>(A + gemm_a_base_elem(m0, M, K, ks0));
+    const char* b_base = reinterpret_cast<const char*>(B + gemm_b_base_elem(n0, N, ks0));
+    const size_t b_step = gemm_b_step_bytes(N);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
     const uint32_t lds_a = lds0 + (uint32_t)(wave * ADMA * 1024);
     const uint32_t lds_b = lds0 + (uint32_t)(kGAElems * 2 + wave * BDMA * 1024);
@@ -229,7 +226,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
         for (int i = 0; i < ADMA; ++i) gemm_dma_load16(a_base, a_off[i], lds_a + so + i * 1024);
-        a_base += kGK * sizeof(__bf16);
+        a_base += gemm_a_step_bytes();
     };
     auto dma_next_b = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
@@ -257,7 +254,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         for (int b = 0; b < 4; ++b) {
             const int krow = 32 * ks + 8 * fg + fi / 4;  // and krow + 4: the same swizzle
             const int col = wn * 64 + 16 * b + 4 * (fi % 4);
-            const int scol = ((col / 8) ^ (4 * (krow % 4) + 2 * ((krow / 8) % 2))) * 8 + col % 8;
+            const int scol = ((col / 8) ^ gemm_b_swz(krow)) * 8 + col % 8;
             const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
             const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
             bfr[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
@@ -597,18 +594,9 @@ static int compute_units() {
     return n;
 }
 
-// Split-K: a product with few output tiles and a long contraction (few active rows) leaves most compute units
-// idle and the few busy ones with a long serial loop. Such a product is cut along K into S parts that run side
-// by side, each writing fp32 sums to scratch, and a second kernel adds the parts in a fixed order and applies
-// the epilogue. Used when the tiles would occupy at most half of the units.
+// Split-K (staging_addr.h: splitk_parts, gemm_plan): each part writes fp32 sums to scratch, and a second kernel
+// adds the parts in a fixed order and applies the epilogue.
 constexpr int kSplitSizingUnits = 256;  // unit count assumed when sizing the scratch (the launch uses the real one)
-constexpr int kSplitMinSteps = 4;       // K steps per part at least
-
-static int splitk_parts(int tiles, int ksteps, int cu) {
-    if (cu <= 0 || 2 * tiles > cu) return 1;
-    const int s = min(cu / tiles, ksteps / kSplitMinSteps);
-    return s < 2 ? 1 : s;
-}
 
 // Scratch bytes that let every product of up to M_cap rows with this K and N split as far as it would like to.
 size_t gemm_splitk_bytes(int M_cap, int K, int N) {
@@ -640,34 +628,23 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
                                                           hipFuncAttributeMaxDynamicSharedMemorySize,
                                                           (int)kGemmSmemBytes);
     if (attr4 != hipSuccess || attr2 != hipSuccess || attr_s != hipSuccess) return DASH_ERR_HIP;
-    const int mt = (M + kGM - 1) / kGM, nt = (N + kGN - 1) / kGN, tiles = mt * nt;
-    const int cu = compute_units(), ksteps = K / kGK;
-    if (split_ws && !delta_dbg) {
-        int parts = splitk_parts(tiles, ksteps, cu);
-        const size_t per_part = (size_t)M * N * sizeof(float);
-        if ((size_t)parts * per_part > split_bytes) parts = (int)(split_bytes / per_part);
-        if (parts >= 2) {
-            const int per = (ksteps + parts - 1) / parts;
-            parts = (ksteps + per - 1) / per;  // every part has at least one K step
-            float* sums = reinterpret_cast<float*>(split_ws);
-            hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(tiles, parts), dim3(kGThreads), kGemmSmemBytes, s,
-                               A, B, M, K, N, nullptr, nullptr, nullptr, sums, mt, 0, per, qkv);
-            const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
-            const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
-            hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((waves * kWave + 255) / 256)), dim3(256), 0,
-                               s, sums, parts, M, N, x, out, partials, qkv);
-            return launch_status();
-        }
+    const GemmPlan g = gemm_plan(M, K, N, compute_units(), split_ws != nullptr && !delta_dbg, split_bytes);
+    if (g.parts >= 2) {
+        float* sums = reinterpret_cast<float*>(split_ws);
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(g.tiles, g.parts), dim3(kGThreads), kGemmSmemBytes, s,
+                           A, B, M, K, N, nullptr, nullptr, nullptr, sums, g.mt, 0, g.ksteps_per_part, qkv);
+        const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
+        const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
+        hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((waves * kWave + 255) / 256)), dim3(256), 0,
+                           s, sums, g.parts, M, N, x, out, partials, qkv);
+        return launch_status();
     }
-    int rest = cu > 0 ? tiles % cu : 0;
-    if (2 * rest > cu) rest = 0;
-    const int full = tiles - rest;
-    if (full > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
-                           out, partials, delta_dbg, mt, 0, ksteps, qkv);
-    if (rest > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
-                           x, out, partials, delta_dbg, mt, full, ksteps, qkv);
+    if (g.full > 0)
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(g.full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
+                           out, partials, delta_dbg, g.mt, 0, g.ksteps, qkv);
+    if (g.rest > 0)
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * g.rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
+                           x, out, partials, delta_dbg, g.mt, g.full, g.ksteps, qkv);
     return launch_status();
 }
 

@@ -1,0 +1,98 @@
+"""CPU check of the staging addresses of the two MFMA kernels: a host library built from the same header the
+kernels use (csrc/staging_addr.h) enumerates every direct global->LDS load of a launch and compares it with
+the clamped row and column the lane is meant to fetch. Shapes: every GEMM and attention shape of the GPU
+tests and the benches, ragged lengths around the tile edges, and seeded random ones."""
+import ctypes
+import os
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PKG = os.path.join(ROOT, "paper_2604_18103_amd")
+CHECK_LIB = os.path.join(PKG, "libdash_staging_check.so")
+
+
+def _load(path=CHECK_LIB):
+    if not os.path.exists(path):
+        pytest.fail("libdash_staging_check.so is not built: run `python -m paper_2604_18103_amd.build`")
+    lib = ctypes.CDLL(path)
+    lib.dash_check_gemm_staging.argtypes = [ctypes.c_int] * 4 + [ctypes.c_ulonglong, ctypes.POINTER(ctypes.c_longlong)]
+    lib.dash_check_gemm_staging.restype = ctypes.c_int
+    lib.dash_check_flash_staging.argtypes = [ctypes.c_int] * 4 + [ctypes.POINTER(ctypes.c_longlong)]
+    lib.dash_check_flash_staging.restype = ctypes.c_int
+    return lib
+
+
+def _gemm(lib, M, K, N, cu=256, split_bytes=0):
+    n = ctypes.c_longlong(0)
+    st = lib.dash_check_gemm_staging(M, K, N, cu, split_bytes, ctypes.byref(n))
+    return st, n.value
+
+
+GEMM_SHAPES = [
+    # (M, K, N): projections, gated feed-forward (N = 2 m), down projection, q/k/v as one product
+    (300, 256, 1024), (300, 512, 256), (333, 256, 256), (1, 64, 64), (1, 3584, 3584), (64, 64, 8),
+    (127, 128, 264), (128, 128, 264), (129, 128, 264), (255, 192, 520), (256, 192, 520), (257, 192, 520),
+    (383, 64, 256), (384, 64, 256), (385, 64, 256), (511, 64, 256), (513, 64, 256),
+    (8192, 3584, 3584), (16384, 3584, 3584), (16384, 3584, 4608), (10976, 3584, 4608), (10976, 18944, 3584),
+    (10976, 3584, 37888), (32768, 3584, 37888), (32768, 18944, 3584), (52428, 4096, 4096), (82, 3584, 3584),
+    (328, 18944, 3584), (2048, 3584, 512),
+]
+
+
+@pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
+def test_gemm_staging_loads_fetch_the_clamped_rows_and_columns(M, K, N):
+    lib = _load()
+    for cu in (256, 304, 64):
+        for split_bytes in (0, 1 << 30):
+            st, n_loads = _gemm(lib, M, K, N, cu, split_bytes)
+            assert st == 0, (M, K, N, cu, split_bytes, st)
+            assert n_loads > 0
+
+
+def test_gemm_staging_seeded_random_shapes():
+    lib = _load()
+    rng = np.random.default_rng(20260418)
+    for _ in range(60):
+        M = int(rng.integers(1, 3000))
+        K = 64 * int(rng.integers(1, 40))
+        N = 8 * int(rng.integers(1, 600))
+        st, _ = _gemm(lib, M, K, N, 256, int(rng.integers(0, 2)) << 30)
+        assert st == 0, (M, K, N, st)
+
+
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 129, 255, 256, 257, 300, 333, 511, 513, 1000, 8192, 10976,
+                               16384, 52428])
+def test_flash_staging_loads_fetch_the_clamped_rows(n):
+    lib = _load()
+    for Hkv, DH in ((4, 128), (8, 128), (1, 64), (2, 64), (1, 128)):
+        for causal in (1, 0):
+            if n > 20000 and (causal == 0 or Hkv != 8):
+                continue
+            cnt = ctypes.c_longlong(0)
+            st = lib.dash_check_flash_staging(n, Hkv, DH, causal, ctypes.byref(cnt))
+            assert st == 0, (n, Hkv, DH, causal, st)
+            assert cnt.value > 0
+
+
+def test_checker_catches_an_unclamped_base_row():
+    """The mistake is planted in a copy of the header on the CPU: with the A base row left unclamped, the second
+    half tile of a 300-row product lies beyond M and its lane offsets wrap; the checker must say so."""
+    src = open(os.path.join(PKG, "csrc", "staging_addr.h")).read()
+    good = "DASH_HD int gemm_a_base_row(int m0, int M) { return sa_min(m0, M - 1); }"
+    assert good in src
+    bad = src.replace(good, "DASH_HD int gemm_a_base_row(int m0, int M) { return m0; }")
+    with tempfile.TemporaryDirectory() as tmp:
+        open(os.path.join(tmp, "staging_addr.h"), "w").write(bad)
+        open(os.path.join(tmp, "staging_check.cpp"), "w").write(open(os.path.join(PKG, "csrc", "staging_check.cpp")).read())
+        out = os.path.join(tmp, "libbad.so")
+        subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", os.path.join(tmp, "staging_check.cpp"),
+                        "-o", out], check=True)
+        lib = _load(out)
+        st, _ = _gemm(lib, 300, 256, 1024)
+        assert st != 0
+        st, _ = _gemm(lib, 512, 256, 1024)      # whole tiles only: the mistake does not show
+        assert st == 0
