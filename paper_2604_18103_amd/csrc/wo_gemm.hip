@@ -628,6 +628,8 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
                                                           hipFuncAttributeMaxDynamicSharedMemorySize,
                                                           (int)kGemmSmemBytes);
     if (attr4 != hipSuccess || attr2 != hipSuccess || attr_s != hipSuccess) return DASH_ERR_HIP;
+    // the staging loads address a tile with 32-bit lane offsets: 256 rows of A, 64 rows of B
+    if ((size_t)kGM * K * 2 >= ((size_t)1 << 32) || (size_t)kGK * N * 2 + 2 * kGN >= ((size_t)1 << 32)) return DASH_ERR_UNSUPPORTED;
     const GemmPlan g = gemm_plan(M, K, N, compute_units(), split_ws != nullptr && !delta_dbg, split_bytes);
     if (g.parts >= 2) {
         float* sums = reinterpret_cast<float*>(split_ws);
