@@ -102,6 +102,13 @@ int dash_check_gemm_staging(int M, int K, int N, int cu, unsigned long long spli
     return c.status;
 }
 
+// The launch decomposition of a product as launch_gemm makes it: out[0..5] = tiles, K steps, parts (>= 2: split-K),
+// K steps per part, whole 256-row tiles, tiles run as 128-row half tiles.
+void dash_gemm_launch_plan(int M, int K, int N, int cu, unsigned long long split_bytes, int* out) {
+    const GemmPlan g = gemm_plan(M, K, N, cu, split_bytes > 0, (size_t)split_bytes);
+    out[0] = g.tiles; out[1] = g.ksteps; out[2] = g.parts; out[3] = g.ksteps_per_part; out[4] = g.full; out[5] = g.rest;
+}
+
 // Checks every K and V staging load of the attention launch over n rows (K, V: [n][Hkv][DH] bf16): for each
 // query tile of 256 rows, the tiles of 64 keys it fetches. Returns 0 when all loads are right.
 int dash_check_flash_staging(int n, int Hkv, int DH, int causal, long long* n_loads) {

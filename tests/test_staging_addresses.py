@@ -96,3 +96,31 @@ def test_checker_catches_an_unclamped_base_row():
         assert st != 0
         st, _ = _gemm(lib, 512, 256, 1024)      # whole tiles only: the mistake does not show
         assert st == 0
+
+
+def test_gemm_launch_plan_whole_rounds_half_tiles_and_k_parts():
+    """How a product is cut into launches on 256 compute units: whole 256-row tiles for the whole rounds, the tiles
+    left over as half tiles when they would fill at most half of the units, K parts when all tiles do."""
+    lib = _load()
+    lib.dash_gemm_launch_plan.argtypes = [ctypes.c_int] * 4 + [ctypes.c_ulonglong, ctypes.POINTER(ctypes.c_int)]
+    lib.dash_gemm_launch_plan.restype = None
+
+    def plan(M, K, N, cu=256, split_bytes=0):
+        out = (ctypes.c_int * 6)()
+        lib.dash_gemm_launch_plan(M, K, N, cu, split_bytes, out)
+        return dict(zip(("tiles", "ksteps", "parts", "per_part", "full", "rest"), out))
+
+    # the bench's projection: 64 x 14 = 896 tiles = 3 whole rounds + 128 tiles as 256 half tiles
+    assert plan(16384, 3584, 3584) == dict(tiles=896, ksteps=56, parts=1, per_part=56, full=768, rest=128)
+    # 8192 rows: 448 tiles; the 192 left over would need more than half of the units twice over: all whole tiles
+    assert plan(8192, 3584, 3584) == dict(tiles=448, ksteps=56, parts=1, per_part=56, full=448, rest=0)
+    # whole rounds only
+    assert plan(32768, 3584, 3584)["rest"] == 0 and plan(32768, 3584, 37888)["rest"] == 0
+    # 177 rows of the down projection (K = 18944): 14 tiles on 256 units -> 18 K parts of at most 17 steps
+    p = plan(177, 18944, 3584, split_bytes=1 << 30)
+    assert p["tiles"] == 14 and p["parts"] == 18 and p["per_part"] == 17 and 17 * 18 >= 296
+    # without scratch, or when the scratch holds one part only, no split
+    assert plan(177, 18944, 3584)["parts"] == 1
+    assert plan(177, 18944, 3584, split_bytes=177 * 3584 * 4)["parts"] == 1
+    # a part never has fewer than 4 K steps: K = 256 (4 steps) cannot split
+    assert plan(64, 256, 256, split_bytes=1 << 30)["parts"] == 1
