@@ -308,18 +308,33 @@ typedef struct {
     int64_t i;
 } scored_row;
 
+/*
+ * Order in which TopK ranks scores. Eq. 3 ranks real numbers; for the values a float can also hold the
+ * reading taken is one total order
+ *     -inf < ... < -0.0 = +0.0 < ... < +inf < NaN        (every NaN equal to every other NaN)
+ * so that the selection is defined for any input: a NaN score ranks highest (the threshold form keeps NaN
+ * rows too: "score < tau" is false for them), and the two zeros tie and are told apart by row like any tie.
+ * Returns -1, 0 or 1.
+ */
+static int score_order(double a, double b) {
+    const int an = isnan(a), bn = isnan(b);
+    if (an || bn) return an - bn;
+    return (a > b) - (a < b);
+}
+
 static int by_score_desc_then_row(const void *a, const void *b) {
     const scored_row *x = (const scored_row *)a, *y = (const scored_row *)b;
-    if (x->s > y->s) return -1;
-    if (x->s < y->s) return 1;
+    const int c = score_order(x->s, y->s);
+    if (c != 0) return -c;
     return (x->i > y->i) - (x->i < y->i);
 }
 
 /*
  * TopK form (Eq. 3): keep k_keep rows in total. Protected rows are always kept
  * and count towards k_keep; of the others, those with the highest scores are
- * kept; among equal scores the earlier row is kept first. If k_keep is not
- * larger than the number of protected rows, every unprotected row halts.
+ * kept (in the order of score_order: NaN above +inf, -0.0 equal to +0.0); among
+ * equal scores the earlier row is kept first. If k_keep is not larger than the
+ * number of protected rows, every unprotected row halts.
  */
 int dash_oracle_decide_topk(const double *scores, int64_t n, int64_t k_keep, int64_t n_first,
                             int64_t n_last, uint8_t *halt) {
@@ -349,14 +364,15 @@ int dash_oracle_decide_topk(const double *scores, int64_t n, int64_t k_keep, int
 
 static int by_score_asc_then_row(const void *a, const void *b) {
     const scored_row *x = (const scored_row *)a, *y = (const scored_row *)b;
-    if (x->s < y->s) return -1;
-    if (x->s > y->s) return 1;
+    const int c = score_order(x->s, y->s);
+    if (c != 0) return c;
     return (x->i > y->i) - (x->i < y->i);
 }
 
 /*
  * The direction control of the ablation (Sec. 5.4, "Directionality"): same budget, but the rows with the LOWEST
- * scores are kept, i.e. the high-Delta tokens halt. Everything else as in dash_oracle_decide_topk. (Random
+ * scores (lowest in the order of score_order, so NaN rows halt first) are kept, i.e. the high-Delta tokens halt.
+ * Everything else as in dash_oracle_decide_topk. (Random
  * halting, the other control, is the ordinary TopK on scores drawn at random by the caller.)
  */
 int dash_oracle_decide_topk_keep_low(const double *scores, int64_t n, int64_t k_keep, int64_t n_first,
@@ -406,13 +422,22 @@ int dash_oracle_compact(const uint8_t *halt, const int32_t *active_idx, const do
 
 /*
  * Number of tokens kept out of n.
- *   paper_impl_rounding == 0 : K = floor((1 - rho) * n)                    (Eq. 3)
+ *   paper_impl_rounding == 0 : K = floor((1 - rho) * n)                    (Eq. 3), as real arithmetic on
+ *                              the decimal rho would give it (see the snap below)
  *   paper_impl_rounding != 0 : n - round(rho * (n - n_first - n_last))     (App. A, Table 5 caption)
  */
 int64_t dash_oracle_keep_count(int64_t n, double rho, int64_t n_first, int64_t n_last,
                                int32_t paper_impl_rounding) {
     if (n < 0 || rho < 0.0 || rho >= 1.0 || n_first < 0 || n_last < 0) return -1;
-    if (!paper_impl_rounding) return (int64_t)floor((1.0 - rho) * (double)n);
+    if (!paper_impl_rounding) {
+        /* floor((1 - rho) n) = n - ceil(rho n) for integer n. rho is a decimal the caller wrote (0.4, 0.667) and
+         * its double is not that decimal: a product that lands within 1e-9 (relative) of an integer is taken
+         * to be that integer, so that rho = 0.667, n = 1000 drops 667 rows, not 668. */
+        double dropped = rho * (double)n;
+        const double nearest = nearbyint(dropped);
+        if (fabs(dropped - nearest) <= 1e-9 * fmax(1.0, fabs(dropped))) dropped = nearest;
+        return n - (int64_t)ceil(dropped);
+    }
     const int64_t n_fix = n_first + n_last;
     if (n <= n_fix) return n;
     const int64_t drop = llround(rho * (double)(n - n_fix));

@@ -231,6 +231,35 @@ def test_topk_ties_keep_earlier_rows():
     np.testing.assert_array_equal(ref.decide_topk(s, 3), [0, 1, 0, 1, 0, 1])
 
 
+def test_topk_orders_nan_above_inf_and_ties_the_two_zeros():
+    """Eq. 3 ranks real numbers; for NaN and signed zeros the reading is one total order
+    -inf < ... < -0.0 = +0.0 < ... < +inf < NaN (all NaNs equal), ties by row. Expected masks written by hand."""
+    inf, nan = np.inf, np.nan
+    #             0     1    2     3     4    5     6     7
+    s = np.array([0.0, nan, -0.0, inf, -1.0, nan, -inf, 0.0])
+    # descending: NaN rows 1, 5 | +inf row 3 | zeros rows 0, 2, 7 (row order: the sign of zero does not rank) |
+    # -1 row 4 | -inf row 6
+    want_order = [1, 5, 3, 0, 2, 7, 4, 6]
+    for K in range(9):
+        want = np.ones(8, dtype=np.uint8)
+        want[want_order[:K]] = 0
+        np.testing.assert_array_equal(ref.decide_topk(s, K), want, err_msg=f"K={K}")
+        # direction control: the lowest in the same order are kept, so NaN rows halt first
+        want_low = np.ones(8, dtype=np.uint8)
+        asc = [6, 4, 0, 2, 7, 3, 1, 5]
+        want_low[asc[:K]] = 0
+        np.testing.assert_array_equal(ref.decide_topk(s, K, keep_low=True), want_low, err_msg=f"low K={K}")
+    # NaNs with different payloads and signs are one value
+    weird = np.array([0x7FF8000000000001, 0xFFF8000000000000, 0x7FF0000000000001], dtype=np.uint64).view(np.float64)
+    s2 = np.concatenate([[5.0], weird, [inf]])
+    np.testing.assert_array_equal(ref.decide_topk(s2, 2), [1, 0, 0, 1, 1])
+    np.testing.assert_array_equal(ref.decide_topk(s2, 4), [1, 0, 0, 0, 0])
+    # a vector of NaNs only and of mixed zeros only: ties by row
+    np.testing.assert_array_equal(ref.decide_topk(np.full(5, nan), 2), [0, 0, 1, 1, 1])
+    np.testing.assert_array_equal(ref.decide_topk(np.array([-0.0, 0.0, -0.0, 0.0]), 3), [0, 0, 0, 1])
+    np.testing.assert_array_equal(ref.decide_topk(np.array([-0.0, 0.0, -0.0, 0.0]), 3, keep_low=True), [0, 0, 0, 1])
+
+
 def test_protected_prefix_and_suffix_never_halt():
     s = np.array([0.0, 0.0, 0.8, 0.1, 0.6, 0.2, 0.0, 0.0])
     np.testing.assert_array_equal(ref.decide_threshold(s, 0.5, 2, 1), [0, 0, 0, 1, 0, 1, 1, 0])
