@@ -274,7 +274,7 @@ def run_aux_kernels_bench(args, cfg):
     from paper_2604_18103_amd import binding as B
 
     n, N, d, Hq, Hkv, dh = cfg.n, cfg.N, cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
-    p = B.make_params(d, Hq, Hkv, dh, causal=True, rule=B.RULE_TOPK, k_keep=n - int(cfg.halt_frac * n))
+    p = B.make_params(d, Hq, Hkv, dh, causal=True, rule=B.RULE_TOPK, k_keep=B.keep_count_quantile(n, cfg.halt_frac))
     g = torch.Generator(device="cuda").manual_seed(cfg.seed)
     bf = torch.bfloat16
     rnd = lambda *shape: torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)

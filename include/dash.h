@@ -8,8 +8,14 @@
  *
  * Conventions for every entry point
  *   - Plain C ABI. Pointers marked "device" are GPU global memory owned by the
- *     caller; "host" pointers are ordinary host memory. The library allocates
- *     nothing and keeps no state between calls.
+ *     caller; "host" pointers are ordinary host memory. The compute entry points
+ *     allocate nothing: every buffer, the workspaces included, is the caller's.
+ *     What the library does keep: (i) per process, the number of compute units of the
+ *     device and the one-time launch attributes of its kernels, set by dash_init() or
+ *     by the first call that needs them (call dash_init() before capturing calls in
+ *     a HIP graph); (ii) dash_profile objects, the only thing it allocates (host
+ *     memory and HIP events, created and destroyed by the caller through
+ *     dash_profile_create / dash_profile_destroy). Results never depend on either.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream); calls return after enqueue and never synchronise.
  *   - Every device pointer must be 16-byte aligned. Matrices are row-major and
@@ -63,7 +69,8 @@ typedef struct {
     float tau;            /* THRESHOLD: a row halts iff score < tau (equal or NaN is kept) */
     int32_t k_keep;       /* TOPK: rows kept in total, protected rows included;
                              < 0 selects floor((1 - rho) * n_active)  (Eq. 3) */
-    float rho;            /* pruning ratio in [0,1), used only when k_keep < 0 */
+    double rho;           /* pruning ratio in [0,1), used only when k_keep < 0; a double, so that the rows kept
+                             are exactly dash_keep_count(n_active, rho, 0, 0, 0) for the caller's rho */
     int32_t keep_first_n; /* protected ranks at the head of the current active order (App. A) */
     int32_t keep_last_n;  /* protected ranks at its tail; protected rows never halt */
 } dash_layer_params;
@@ -73,6 +80,11 @@ typedef struct {
  * with dash_profile_read after the stream has been synchronised by the caller. */
 typedef struct dash_profile dash_profile;
 #define DASH_N_STAGES 4 /* 0 flash attention, 1 W_o+residual+norms, 2 score+decision, 3 compaction */
+
+/* One-time set-up on the current device: reads the device's compute-unit count and sets the launch attributes of
+ * the kernels (their LDS sizes). Optional: the first compute call does the same. Synchronous, host; launches
+ * nothing. Returns DASH_ERR_HIP when there is no usable device. */
+dash_status dash_init(void);
 
 dash_profile *dash_profile_create(void);            /* host; NULL on failure */
 void dash_profile_destroy(dash_profile *);          /* host */
@@ -221,11 +233,40 @@ dash_status dash_validate_active_idx(const int32_t *active_idx, int32_t n, int32
                                      void *hip_stream);
 
 /* Host arithmetic: tokens kept out of n.
- * paper_impl_rounding == 0: floor((1 - rho) n) (Eq. 3);
+ * paper_impl_rounding == 0: floor((1 - rho) n) (Eq. 3), evaluated as n - ceil(rho n) with a product that lies
+ * within 1e-9 (relative) of a whole number taken as that number, so that decimal ratios give what exact
+ * arithmetic on the decimal gives (rho = 0.667, n = 1000 keeps 333);
  * otherwise n - round(rho * (n - keep_first_n - keep_last_n)) (App. A, caption of Table 5).
  * Returns -1 on invalid arguments. */
 int64_t dash_keep_count(int64_t n, double rho, int32_t keep_first_n, int32_t keep_last_n,
                         int32_t paper_impl_rounding);
+
+/* Host arithmetic: rows kept when the h = floor(halt_frac * n) lowest-scoring rows halt (a cut at the halt_frac
+ * quantile of the scores, the TopK equivalent of a threshold drawn at that quantile as in Fig. 8): n - h.
+ * halt_frac in [0,1]; returns -1 on invalid arguments. */
+int64_t dash_keep_count_quantile(int64_t n, double halt_frac);
+
+/* Host arithmetic of the prefill cost model (App. A).
+ *  - dash_block_cost: the per-block proxy A(n) = 4 n d^2 + 2 n^2 d + 2 n d m (Eq. 4), d hidden size, m FFN width.
+ *  - dash_schedule_lengths: lengths[l] = rows block l runs on, l = 0..L-1, for a prompt of n tokens when halting
+ *    decisions are taken after the blocks shot_blocks[0..n_shots) (strictly increasing, each in [0, L)) with
+ *    compression ratios shot_ratios[i]: the deciding block still runs on all rows that enter it (Alg. 1 takes the
+ *    decision after the block's FFN), the blocks after it on dash_keep_count(rows, ratio, keep_first_n,
+ *    keep_last_n, 1) rows (App. A's rule on the current length). One shot at l_s is the single-shot schedule.
+ *  - dash_schedule_cost: sum over the blocks of A(lengths[l]); for one shot this is l_s A(n) + (L - l_s) A(n^)
+ *    (Eq. 6-7 with C_full = dash_schedule_cost of the schedule without shots).
+ *  - dash_comparable_multi_shot_ratio: the smallest ratio c = i / grid (i = 0..grid) such that the schedule
+ *    that applies c at every block of shot_blocks costs no more than target_cost (App. D compares single- and
+ *    multi-shot selection "under comparable budgets" without giving the split; this is the reading taken).
+ *    Returns -1 when no ratio on the grid meets the budget or on invalid arguments.
+ * dash_schedule_lengths returns DASH_ERR_INVALID_ARG for bad arguments; the cost functions return -1. */
+double dash_block_cost(double n, double d, double m);
+dash_status dash_schedule_lengths(int64_t n, int32_t L, const int32_t *shot_blocks, const double *shot_ratios,
+                                  int32_t n_shots, int32_t keep_first_n, int32_t keep_last_n, int64_t *lengths);
+double dash_schedule_cost(const int64_t *lengths, int32_t L, double d, double m);
+double dash_comparable_multi_shot_ratio(int64_t n, int32_t L, const int32_t *shot_blocks, int32_t n_shots,
+                                        double target_cost, double d, double m, int32_t keep_first_n,
+                                        int32_t keep_last_n, int32_t grid);
 
 /* Algorithmic floating-point operations of stages 0+1 for n active rows: causal triangle
  * 4*dh*Hq*n(n+1)/2 (or the full square when not causal) plus 2*n*(Hq*dh)*d. Host. */

@@ -31,7 +31,7 @@ class LayerParams(C.Structure):
     _fields_ = [("d", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("dtype", C.c_int32), ("causal", C.c_int32),
                 ("softmax_scale", C.c_float), ("rule", C.c_int32), ("score_kind", C.c_int32),
-                ("tau", C.c_float), ("k_keep", C.c_int32), ("rho", C.c_float),
+                ("tau", C.c_float), ("k_keep", C.c_int32), ("rho", C.c_double),
                 ("keep_first_n", C.c_int32), ("keep_last_n", C.c_int32)]
 
 
@@ -54,6 +54,20 @@ def lib() -> C.CDLL:
     L.dash_version.restype = C.c_char_p
     L.dash_keep_count.restype = C.c_int64
     L.dash_keep_count.argtypes = [C.c_int64, C.c_double, C.c_int32, C.c_int32, C.c_int32]
+    L.dash_init.restype = C.c_int
+    L.dash_init.argtypes = []
+    L.dash_keep_count_quantile.restype = C.c_int64
+    L.dash_keep_count_quantile.argtypes = [C.c_int64, C.c_double]
+    L.dash_block_cost.restype = C.c_double
+    L.dash_block_cost.argtypes = [C.c_double] * 3
+    L.dash_schedule_lengths.restype = C.c_int
+    L.dash_schedule_lengths.argtypes = [C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_double), C.c_int32,
+                                        C.c_int32, C.c_int32, C.POINTER(C.c_int64)]
+    L.dash_schedule_cost.restype = C.c_double
+    L.dash_schedule_cost.argtypes = [C.POINTER(C.c_int64), C.c_int32, C.c_double, C.c_double]
+    L.dash_comparable_multi_shot_ratio.restype = C.c_double
+    L.dash_comparable_multi_shot_ratio.argtypes = [C.c_int64, C.c_int32, C.POINTER(C.c_int32), C.c_int32, C.c_double,
+                                                   C.c_double, C.c_double, C.c_int32, C.c_int32, C.c_int32]
     L.dash_layer_flops.restype = C.c_double
     L.dash_layer_flops.argtypes = [pp, C.c_int64]
     L.dash_norm_partials_per_row.restype = C.c_int32
@@ -123,6 +137,47 @@ def make_params(d, n_q_heads, n_kv_heads, head_dim, dtype=DASH_BF16, causal=True
 def keep_count(n, rho, keep_first_n=0, keep_last_n=0, paper_impl_rounding=False) -> int:
     return int(lib().dash_keep_count(int(n), float(rho), int(keep_first_n), int(keep_last_n),
                                      int(bool(paper_impl_rounding))))
+
+
+def init() -> None:
+    """One-time set-up of the library on the current device (needed before capturing calls in a HIP graph)."""
+    _check(lib().dash_init(), "dash_init")
+
+
+def keep_count_quantile(n, halt_frac) -> int:
+    return int(lib().dash_keep_count_quantile(int(n), float(halt_frac)))
+
+
+def block_cost(n, d, m) -> float:
+    return float(lib().dash_block_cost(float(n), float(d), float(m)))
+
+
+def schedule_lengths(n, L, ratios: dict, keep_first_n=0, keep_last_n=0) -> list:
+    """Rows each of L blocks runs on when the decision after block l applies compression ratio ratios[l]."""
+    blocks = sorted(int(l) for l in ratios)
+    nb = len(blocks)
+    b_arr = (C.c_int32 * max(nb, 1))(*blocks)
+    r_arr = (C.c_double * max(nb, 1))(*[float(ratios[l]) for l in blocks])
+    out = (C.c_int64 * max(int(L), 1))()
+    _check(lib().dash_schedule_lengths(int(n), int(L), b_arr, r_arr, nb, int(keep_first_n), int(keep_last_n), out),
+           "dash_schedule_lengths")
+    return [int(out[l]) for l in range(int(L))]
+
+
+def schedule_cost(lengths, d, m) -> float:
+    arr = (C.c_int64 * max(len(lengths), 1))(*[int(t) for t in lengths])
+    return float(lib().dash_schedule_cost(arr, len(lengths), float(d), float(m)))
+
+
+def comparable_multi_shot_ratio(n, L, shot_blocks, target_cost, d, m, keep_first_n=0, keep_last_n=0,
+                                grid=10000) -> float:
+    blocks = sorted(int(l) for l in shot_blocks)
+    b_arr = (C.c_int32 * max(len(blocks), 1))(*blocks)
+    c = float(lib().dash_comparable_multi_shot_ratio(int(n), int(L), b_arr, len(blocks), float(target_cost), float(d),
+                                                     float(m), int(keep_first_n), int(keep_last_n), int(grid)))
+    if c < 0.0:
+        raise ValueError("no ratio on the grid meets the budget")
+    return c
 
 
 def layer_flops(params: LayerParams, n: int) -> float:

@@ -53,7 +53,7 @@ def run_chain(state: ChainState, x0: torch.Tensor, active_idx0: torch.Tensor, n0
     out = []
     for l, W in enumerate(weights):
         buf = state.bufs[l & 1]
-        p.k_keep = n - int(halt_frac * n)        # halt the floor(f n) lowest scores
+        p.k_keep = B.keep_count_quantile(n, halt_frac)        # halt the floor(f n) lowest scores
         if time_layers:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()

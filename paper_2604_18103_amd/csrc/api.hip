@@ -28,7 +28,7 @@ dash_status check_params(const dash_layer_params* p) {
         return DASH_ERR_INVALID_ARG;
     if (p->score_kind != DASH_SCORE_REL && p->score_kind != DASH_SCORE_ABS) return DASH_ERR_INVALID_ARG;
     if (p->keep_first_n < 0 || p->keep_last_n < 0) return DASH_ERR_INVALID_ARG;
-    if (p->rule == DASH_RULE_TOPK && p->k_keep < 0 && !(p->rho >= 0.f && p->rho < 1.f))
+    if (p->rule == DASH_RULE_TOPK && p->k_keep < 0 && !(p->rho >= 0.0 && p->rho < 1.0))
         return DASH_ERR_INVALID_ARG;
     return DASH_OK;
 }
@@ -76,10 +76,82 @@ const char* dash_version(void) { return "libdash 0.1 (gfx950)"; }
 int64_t dash_keep_count(int64_t n, double rho, int32_t keep_first_n, int32_t keep_last_n,
                         int32_t paper_impl_rounding) {
     if (n < 0 || !(rho >= 0.0 && rho < 1.0) || keep_first_n < 0 || keep_last_n < 0) return -1;
-    if (!paper_impl_rounding) return (int64_t)floor((1.0 - rho) * (double)n);
+    if (!paper_impl_rounding) {
+        // Eq. 3 as n - ceil(rho n); a product within 1e-9 (relative) of a whole number counts as that number,
+        // because the double of a decimal ratio (0.4, 0.667) sits a hair beside it
+        double drop = rho * (double)n;
+        const double whole = round(drop);
+        if (fabs(drop - whole) <= 1e-9 * fmax(1.0, fabs(drop))) drop = whole;
+        return n - (int64_t)ceil(drop);
+    }
     const int64_t n_fix = (int64_t)keep_first_n + keep_last_n;
     if (n <= n_fix) return n;
     return n - llround(rho * (double)(n - n_fix));
+}
+
+int64_t dash_keep_count_quantile(int64_t n, double halt_frac) {
+    if (n < 0 || !(halt_frac >= 0.0 && halt_frac <= 1.0)) return -1;
+    return n - (int64_t)floor(halt_frac * (double)n);
+}
+
+double dash_block_cost(double n, double d, double m) {
+    if (!(n >= 0.0) || !(d > 0.0) || !(m >= 0.0)) return -1.0;
+    return 4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m;
+}
+
+dash_status dash_schedule_lengths(int64_t n, int32_t L, const int32_t* shot_blocks, const double* shot_ratios,
+                                  int32_t n_shots, int32_t keep_first_n, int32_t keep_last_n, int64_t* lengths) {
+    if (n < 0 || L < 0 || n_shots < 0 || !lengths || keep_first_n < 0 || keep_last_n < 0) return DASH_ERR_INVALID_ARG;
+    if (n_shots > 0 && (!shot_blocks || !shot_ratios)) return DASH_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n_shots; ++i) {
+        if (shot_blocks[i] < 0 || shot_blocks[i] >= L || (i > 0 && shot_blocks[i] <= shot_blocks[i - 1]))
+            return DASH_ERR_INVALID_ARG;
+        if (!(shot_ratios[i] >= 0.0 && shot_ratios[i] < 1.0)) return DASH_ERR_INVALID_ARG;
+    }
+    int64_t cur = n;
+    int32_t next = 0;
+    for (int32_t l = 0; l < L; ++l) {
+        lengths[l] = cur;
+        if (next < n_shots && shot_blocks[next] == l) {
+            cur = dash_keep_count(cur, shot_ratios[next], keep_first_n, keep_last_n, 1);
+            ++next;
+        }
+    }
+    return DASH_OK;
+}
+
+double dash_schedule_cost(const int64_t* lengths, int32_t L, double d, double m) {
+    if (!lengths || L < 0 || !(d > 0.0) || !(m >= 0.0)) return -1.0;
+    double c = 0.0;
+    for (int32_t l = 0; l < L; ++l) c += dash_block_cost((double)lengths[l], d, m);
+    return c;
+}
+
+double dash_comparable_multi_shot_ratio(int64_t n, int32_t L, const int32_t* shot_blocks, int32_t n_shots,
+                                        double target_cost, double d, double m, int32_t keep_first_n,
+                                        int32_t keep_last_n, int32_t grid) {
+    if (n < 0 || L <= 0 || L > 4096 || n_shots <= 0 || n_shots > L || !shot_blocks || grid <= 0) return -1.0;
+    int64_t lengths[4096];
+    double ratios[4096];
+    // the cost falls (weakly) as the ratio grows: bisection for the smallest grid point within the budget
+    auto cost = [&](int32_t i) {
+        const double c = (double)i / (double)grid;
+        for (int32_t s = 0; s < n_shots; ++s) ratios[s] = c;
+        if (dash_schedule_lengths(n, L, shot_blocks, ratios, n_shots, keep_first_n, keep_last_n, lengths) != DASH_OK)
+            return -1.0;
+        return dash_schedule_cost(lengths, L, d, m);
+    };
+    int32_t lo = 0, hi = grid - 1;   // ratio 1 itself is not a valid compression ratio
+    const double c_hi = cost(hi);
+    if (c_hi < 0.0 || c_hi > target_cost) return -1.0;
+    while (lo < hi) {
+        const int32_t mid = lo + (hi - lo) / 2;
+        if (cost(mid) <= target_cost)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    return (double)lo / (double)grid;
 }
 
 double dash_layer_flops(const dash_layer_params* p, int64_t n) {
@@ -97,6 +169,12 @@ int32_t dash_norm_partials_per_row(const dash_layer_params* p) {
 size_t dash_workspace_bytes(const dash_layer_params* p, int32_t n_capacity) {
     if (check_params(p) != DASH_OK || n_capacity < 0) return 0;
     return carve(*p, n_capacity).total;
+}
+
+dash_status dash_init(void) {
+    dash_status st = init_flash_kernels();
+    if (st != DASH_OK) return st;
+    return init_gemm_kernels();
 }
 
 dash_profile* dash_profile_create(void) {
@@ -178,6 +256,7 @@ dash_status dash_decide_topk(const dash_layer_params* p, const float* scores, in
     if (n < 0) return DASH_ERR_INVALID_ARG;
     if (n == 0) return DASH_OK;
     if (!scores || !halt_mask || !chunk_keep_counts) return DASH_ERR_INVALID_ARG;
+    if (p->k_keep < 0 && !(p->rho >= 0.0 && p->rho < 1.0)) return DASH_ERR_INVALID_ARG;
     const size_t need = decide_workspace_bytes() + (size_t)((n + kChunkRows - 1) / kChunkRows) * 4;
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DASH_ERR_WORKSPACE;
     return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace,

@@ -45,6 +45,10 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // ---- stage launchers (implemented in the .hip files; all arguments validated by the caller) ----
 
+// one-time set-up of the MFMA kernels (idempotent; also run by the first launch)
+dash_status init_flash_kernels();
+dash_status init_gemm_kernels();
+
 // flash_fwd.hip
 dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const void* k, const void* v,
                              const int32_t* active_idx, int n, void* o, hipStream_t s);

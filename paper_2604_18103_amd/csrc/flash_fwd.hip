@@ -522,6 +522,18 @@ static dash_status launch_simple(const dash_layer_params& p, const T* q, const T
     return launch_status();
 }
 
+// One-time launch attribute of the MFMA kernels: their dynamic LDS size.
+dash_status init_flash_kernels() {
+    static const hipError_t err = [] {
+        hipError_t e = hipFuncSetAttribute((const void*)flash_fwd_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)FaSmem<64>::BYTES);
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute((const void*)flash_fwd_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)FaSmem<128>::BYTES);
+    }();
+    return err == hipSuccess ? DASH_OK : DASH_ERR_HIP;
+}
+
 dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const void* k, const void* v,
                              const int32_t* active_idx, int n, void* o, hipStream_t s) {
     if (n == 0) return DASH_OK;
@@ -546,17 +558,12 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
         blocks = 8u * (unsigned)(mp.items_per_g * mp.g_per_xcd);
     }
     const dim3 grid(blocks);
+    if (init_flash_kernels() != DASH_OK) return DASH_ERR_HIP;
     if (p.head_dim == 64) {
-        static const hipError_t attr64 = hipFuncSetAttribute(
-            (const void*)flash_fwd_mfma<64>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<64>::BYTES);
-        if (attr64 != hipSuccess) return DASH_ERR_HIP;
         hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(kFaThreads), FaSmem<64>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
                            p.causal, n_qtiles, mp);
     } else {
-        static const hipError_t attr128 = hipFuncSetAttribute(
-            (const void*)flash_fwd_mfma<128>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)FaSmem<128>::BYTES);
-        if (attr128 != hipSuccess) return DASH_ERR_HIP;
         hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(kFaThreads), FaSmem<128>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
                            p.causal, n_qtiles, mp);

@@ -71,9 +71,14 @@ __global__ __launch_bounds__(256) void score_only_kernel(const float* __restrict
     if (threadIdx.x < kChunkRows && row < n) scores[row] = score_from_sums(t, score_kind);
 }
 
-// Order-preserving map from fp32 to uint32 (larger float -> larger key; positive NaN above +inf).
+// Order-preserving map from fp32 to uint32 for the total order in which TopK ranks scores:
+//   -inf < ... < -0.0 = +0.0 < ... < +inf < NaN   (every NaN, whatever its sign or payload, is one value).
+// Eq. 3 ranks real numbers; this is the reading for the other values a float can hold: a NaN score ranks highest
+// (the threshold rule keeps NaN rows as well, "score < tau" being false), the two zeros tie and are told apart
+// by row like any tie.
 __device__ __forceinline__ uint32_t order_key(float f) {
-    const uint32_t b = __float_as_uint(f);
+    if (f != f) return 0xFFFFFFFFu;
+    const uint32_t b = __float_as_uint(f == 0.0f ? 0.0f : f);
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
@@ -287,7 +292,7 @@ dash_status launch_score_decide(const dash_layer_params& p, const float* partial
         return launch_status();
     }
     int64_t k_keep = p.k_keep;
-    if (k_keep < 0) k_keep = dash_keep_count(n, (double)p.rho, 0, 0, 0);
+    if (k_keep < 0) k_keep = dash_keep_count(n, p.rho, 0, 0, 0);
     if (k_keep > n) k_keep = n;
     TopkState* st = reinterpret_cast<TopkState*>(ws);
     int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
@@ -307,7 +312,7 @@ dash_status launch_decide_topk(const dash_layer_params& p, const float* scores, 
                                int32_t* chunk_counts, void* ws, hipStream_t s) {
     if (n == 0) return DASH_OK;
     int64_t k_keep = p.k_keep;
-    if (k_keep < 0) k_keep = dash_keep_count(n, (double)p.rho, 0, 0, 0);
+    if (k_keep < 0) k_keep = dash_keep_count(n, p.rho, 0, 0, 0);
     if (k_keep > n) k_keep = n;
     TopkState* st = reinterpret_cast<TopkState*>(ws);
     int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);

@@ -594,6 +594,28 @@ static int compute_units() {
     return n;
 }
 
+// One-time launch attribute of every instantiation of the MFMA kernel: its 128 KB of dynamic LDS.
+template <int EPI>
+static hipError_t set_gemm_lds_size() {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmSmemBytes);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)kGemmSmemBytes);
+}
+
+dash_status init_gemm_kernels() {
+    static const hipError_t err = [] {
+        hipError_t e = set_gemm_lds_size<EPI_RESIDUAL_NORM>();
+        if (e == hipSuccess) e = set_gemm_lds_size<EPI_STORE>();
+        if (e == hipSuccess) e = set_gemm_lds_size<EPI_SWIGLU>();
+        if (e == hipSuccess) e = set_gemm_lds_size<EPI_SPLITK>();
+        if (e == hipSuccess) e = set_gemm_lds_size<EPI_QKV>();
+        return e;
+    }();
+    return err == hipSuccess && compute_units() > 0 ? DASH_OK : DASH_ERR_HIP;
+}
+
 // Split-K (staging_addr.h: splitk_parts, gemm_plan): each part writes fp32 sums to scratch, and a second kernel
 // adds the parts in a fixed order and applies the epilogue.
 constexpr int kSplitSizingUnits = 256;  // unit count assumed when sizing the scratch (the launch uses the real one)
@@ -618,16 +640,7 @@ template <int EPI>
 static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
                                __bf16* out, float* partials, float* delta_dbg, void* split_ws, size_t split_bytes,
                                hipStream_t s, QkvOut qkv = QkvOut{nullptr, nullptr, 0, 0}) {
-    static const hipError_t attr4 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         (int)kGemmSmemBytes);
-    static const hipError_t attr2 = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 2>,
-                                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                         (int)kGemmSmemBytes);
-    static const hipError_t attr_s = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI_SPLITK, 4>,
-                                                          hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                          (int)kGemmSmemBytes);
-    if (attr4 != hipSuccess || attr2 != hipSuccess || attr_s != hipSuccess) return DASH_ERR_HIP;
+    if (init_gemm_kernels() != DASH_OK) return DASH_ERR_HIP;
     // the staging loads address a tile with 32-bit lane offsets: 256 rows of A, 64 rows of B
     if ((size_t)kGM * K * 2 >= ((size_t)1 << 32) || (size_t)kGK * N * 2 + 2 * kGN >= ((size_t)1 << 32)) return DASH_ERR_UNSUPPORTED;
     const GemmPlan g = gemm_plan(M, K, N, compute_units(), split_ws != nullptr && !delta_dbg, split_bytes);

@@ -138,7 +138,8 @@ class GraphedSchedule:
                  final: torch.Tensor | None = None):
         self.final = torch.empty_like(x0) if final is None else final
         args = dict(rope_theta=rope_theta, final=self.final, read_counts=False)
-        run_schedule(st, x0, weights, shots, **args)           # eager once: one-time set-up of the library
+        B.init()                                               # one-time set-up of the library, outside the capture
+        run_schedule(st, x0, weights, shots, **args)           # eager once: torch's own lazy set-up
         torch.cuda.synchronize()
         self.graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(self.graph):
@@ -159,36 +160,8 @@ def run_single_shot(st: BlockState, x0: torch.Tensor, weights: list, l_s: int | 
     return run_schedule(st, x0, weights, shots, rope_theta=rope_theta, final=final, on_block=on_block)
 
 
-def block_cost(n, d, m) -> float:
-    """Per-block prefill FLOPs proxy A(n) = 4 n d^2 + 2 n^2 d + 2 n d m of App. A."""
-    n, d, m = float(n), float(d), float(m)
-    return 4.0 * n * d * d + 2.0 * n * n * d + 2.0 * n * d * m
-
-
-def schedule_lengths(n, L, ratios: dict, n_first=0, n_last=0) -> list:
-    """Rows each of L blocks runs on when block l applies compression ratio ratios[l] to the rows that enter it
-    (kept count by App. A's rule on the current length; the deciding block itself still runs on all of them)."""
-    out, cur = [], int(n)
-    for l in range(int(L)):
-        out.append(cur)
-        if l in ratios:
-            cur = B.keep_count(cur, ratios[l], n_first, n_last, paper_impl_rounding=True)
-    return out
-
-
-def comparable_multi_shot_ratio(n, L, shot_layers, target_cost, d, m, n_first=0, n_last=0, grid=10000) -> float:
-    """Common per-shot compression ratio (a multiple of 1 / grid) of a multi-shot schedule whose App. A cost does
-    not exceed target_cost: the smallest such ratio, found by bisection (the cost falls as the ratio grows)."""
-    def cost(i):
-        c = i / grid
-        return sum(block_cost(t, d, m) for t in schedule_lengths(n, L, {l: c for l in shot_layers}, n_first, n_last))
-    lo, hi = 0, grid
-    if cost(hi) > target_cost:
-        raise ValueError("no ratio on the grid meets the budget")
-    while lo < hi:
-        mid = (lo + hi) // 2
-        if cost(mid) <= target_cost:
-            hi = mid
-        else:
-            lo = mid + 1
-    return lo / grid
+# Host arithmetic of App. A's cost model and of the schedules lives in the library (include/dash.h); these names
+# are kept for the callers of this module.
+block_cost = B.block_cost
+schedule_lengths = B.schedule_lengths
+comparable_multi_shot_ratio = B.comparable_multi_shot_ratio
