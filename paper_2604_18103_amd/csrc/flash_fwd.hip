@@ -218,11 +218,29 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc) Qf[kc] = *reinterpret_cast<const bf16x8*>(qp + 16 * kc);
         // Q is scaled once by softmax_scale * log2(e) (rounded to bf16 again), so the MFMA result is already the
-        // exponent in the log2 domain
+        // exponent in the log2 domain. Rounding the scaled row r = bf16(x) changes its length along x by the
+        // factor <r, x> / <x, x>, which acts on every logit of the row like a change of the softmax temperature
+        // and, for a fixed scale constant, has a common sign for most rows (measured: 3e-4 of systematic relative
+        // error in ||delta||). The row is therefore rounded a second time from x scaled by the inverse of that
+        // factor, which cancels the systematic part; what is left is the random part of one rounding.
+        float xs[KC][8];
+        float sxx = 0.f, srx = 0.f;
 #pragma unroll
         for (int kc = 0; kc < KC; ++kc)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) Qf[kc][e] = (__bf16)((float)Qf[kc][e] * scale_log2);
+            for (int e = 0; e < 8; ++e) {
+                const float x = (float)Qf[kc][e] * scale_log2;
+                xs[kc][e] = x;
+                sxx = fmaf(x, x, sxx);
+                srx = fmaf((float)(__bf16)x, x, srx);
+            }
+        sxx += __shfl_xor(sxx, 32);  // lanes j and j + 32 hold the two halves of the row
+        srx += __shfl_xor(srx, 32);
+        const float comp = sxx > 0.f ? 2.0f - srx / sxx : 1.0f;  // 1 / (1 + a) to first order, a = srx / sxx - 1
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Qf[kc][e] = (__bf16)(xs[kc][e] * comp);
     }
     f32x16 Oacc[DB];
 #pragma unroll

@@ -17,7 +17,30 @@ from paper_2604_18103_amd import binding as B
 from paper_2604_18103_amd import inputs as I
 
 X_TOL = {"bf16": 2e-2, "f32": 1e-5}
-SCORE_TOL = {"bf16": 5e-3, "f32": 1e-5}   # informational bound, far inside the 1e-3 band only for fp32
+
+
+def score_tol(cfg):
+    """(bound on the largest, bound on the mean) relative score error over the rows compared.
+    fp32: rounding of the sums. bf16: the probabilities enter the P V product as bf16, so a row whose attention sits
+    on one or two keys carries their rounding (up to 2^-9 each) straight into ||delta||: about one row in ten
+    thousand reaches 1e-3 (measured 1.02e-3 over the 8192 rows of the N = 8192 configuration, reproduced by emulating
+    the roundings in numpy), while the mean stays below 1e-4 at the benchmark width 3584 (the second rounding of the
+    scaled query, which used to add a systematic 3e-4, is compensated in the kernel). Both figures fall like
+    1 / sqrt(Hq * dh), the error averaging over heads and dims, so narrower test shapes get them scaled up."""
+    if cfg.dtype != "bf16":
+        return 1e-5, 1e-5
+    f = max(1.0, (3584.0 / (cfg.n_q_heads * cfg.head_dim)) ** 0.5)
+    return 2e-3 * f, 2e-4 * f
+
+
+def check_scores(cfg, got, want):
+    serr = np.abs(np.asarray(got, dtype=np.float64) - want) / np.maximum(np.abs(want), 1e-300)
+    tol_max, tol_mean = score_tol(cfg)
+    assert serr.max() <= tol_max, f"score rel err {serr.max():.3e} at {int(serr.argmax())}"
+    assert serr.mean() <= tol_mean, f"mean score rel err {serr.mean():.3e}"
+    return serr
+
+
 BAND_REL = 1e-3
 
 
@@ -83,9 +106,9 @@ def compare_with_oracle(cfg, g: GpuResult, o: ref.LayerResult, tau, active_idx, 
     rows = np.arange(g.x_next.shape[0]) if rows is None else np.asarray(rows)
     xerr = row_rel_err(g.x_next[rows], o.x_next)
     assert xerr.max() <= X_TOL[cfg.dtype], f"x_next rel err {xerr.max():.3e} at row {rows[xerr.argmax()]}"
-    serr = np.abs(g.scores[rows].astype(np.float64) - o.scores) / np.maximum(np.abs(o.scores), 1e-300)
-    assert serr.max() <= SCORE_TOL[cfg.dtype], f"score rel err {serr.max():.3e}"
-    report = dict(x_next_max_rel=float(xerr.max()), score_max_rel=float(serr.max()), band_rows=0)
+    serr = check_scores(cfg, g.scores[rows], o.scores)
+    report = dict(x_next_max_rel=float(xerr.max()), score_max_rel=float(serr.max()),
+                  score_mean_rel=float(serr.mean()), band_rows=0)
     if tau is not None:
         band = np.abs(o.scores - tau) <= BAND_REL * abs(tau)
         want_halt = (o.scores < tau).astype(np.uint8) if o.halt is None else o.halt
