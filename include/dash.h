@@ -82,7 +82,8 @@ typedef struct dash_profile dash_profile;
 #define DASH_N_STAGES 4 /* 0 flash attention, 1 W_o+residual+norms, 2 score+decision, 3 compaction */
 
 /* One-time set-up on the current device: reads the device's compute-unit count and sets the launch attributes of
- * the kernels (their LDS sizes). Optional: the first compute call does the same. Synchronous, host; launches
+ * the kernels (their LDS sizes) and looks up the device address of the static scratch of dash_decide_topk_static.
+ * Optional: the first compute call that needs one of these does the same. Synchronous, host; launches
  * nothing. Returns DASH_ERR_HIP when there is no usable device. */
 dash_status dash_init(void);
 
@@ -178,6 +179,20 @@ dash_status dash_score_diff_rows(const void *x_new, const void *x_old, int32_t n
 dash_status dash_decide_topk(const dash_layer_params *params, const float *scores, int32_t n, int32_t keep_low,
                              uint8_t *halt_mask, int32_t *chunk_keep_counts, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+
+/* dash_decide_topk for callers that cannot allocate or pass device scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. Same decision, same outputs (bit for bit), no workspace argument:
+ * the selection state and tie counts live in a device array that is part of the library image
+ * (256 + 4 * DASH_TOPK_STATIC_MAX_ROWS / 64 bytes = 65 792 bytes on every GPU the library runs on, held until the
+ * process ends). Allocates nothing and frees nothing. n > DASH_TOPK_STATIC_MAX_ROWS returns DASH_ERR_UNSUPPORTED.
+ * The first call on a device (or dash_init() with that device current) looks up the array's device address; do
+ * that outside a graph capture. All calls on one GPU share that GPU's array, which keeps the last call's contents
+ * (the kernels overwrite what they read, nothing needs clearing): calls that overlap on one GPU (different
+ * streams, or threads) race; calls on one stream are ordered and safe. */
+#define DASH_TOPK_STATIC_MAX_ROWS (1 << 20)
+dash_status dash_decide_topk_static(const dash_layer_params *params, const float *scores, int32_t n,
+                                    int32_t keep_low, uint8_t *halt_mask, int32_t *chunk_keep_counts,
+                                    void *hip_stream);
 
 /* Front end of a layer in a chain (Eq. 1's LN and the q/k/v projections, which sit before the path):
  * h = x / sqrt(mean(x^2) + 1e-6) (unit gain); q = h @ w_q [d, Hq*dh]; k = h @ w_k; v = h @ w_v

@@ -94,6 +94,8 @@ def lib() -> C.CDLL:
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_score_diff_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_decide_topk.argtypes = [pp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.dash_decide_topk_static.argtypes = [pp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp]
+    L.dash_decide_topk_static.restype = C.c_int
     L.dash_ffn_workspace_bytes.restype = C.c_size_t
     L.dash_ffn_workspace_bytes.argtypes = [pp, C.c_int32, C.c_int32]
     L.dash_ffn_swiglu.argtypes = [pp, _vp, _vp, _vp, C.c_int32, C.c_int32, _vp, _vp, C.c_size_t, _vp]
@@ -298,6 +300,15 @@ def dash_decide_topk(params, scores, n, keep_low, halt_mask, chunk_keep_counts, 
     _check(lib().dash_decide_topk(C.byref(params), _p(scores), int(n), int(bool(keep_low)), _p(halt_mask),
                                   _p(chunk_keep_counts), _p(workspace), workspace.numel(), _stream()),
            "dash_decide_topk")
+
+
+TOPK_STATIC_MAX_ROWS = 1 << 20
+
+
+def dash_decide_topk_static(params, scores, n, keep_low, halt_mask, chunk_keep_counts) -> None:
+    """dash_decide_topk without a workspace argument (the library's static device scratch); allocates nothing."""
+    _check(lib().dash_decide_topk_static(C.byref(params), _p(scores), int(n), int(bool(keep_low)), _p(halt_mask),
+                                         _p(chunk_keep_counts), _stream()), "dash_decide_topk_static")
 
 
 def ffn_workspace_bytes(params: LayerParams, n_capacity: int, m: int) -> int:

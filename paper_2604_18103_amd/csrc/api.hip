@@ -174,7 +174,10 @@ size_t dash_workspace_bytes(const dash_layer_params* p, int32_t n_capacity) {
 dash_status dash_init(void) {
     dash_status st = init_flash_kernels();
     if (st != DASH_OK) return st;
-    return init_gemm_kernels();
+    st = init_gemm_kernels();
+    if (st != DASH_OK) return st;
+    void* scratch = nullptr;
+    return topk_static_scratch_ptr(&scratch);  // device address of the static TopK scratch on the current device
 }
 
 dash_profile* dash_profile_create(void) {
@@ -261,6 +264,22 @@ dash_status dash_decide_topk(const dash_layer_params* p, const float* scores, in
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DASH_ERR_WORKSPACE;
     return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace,
                               (hipStream_t)hip_stream);
+}
+
+dash_status dash_decide_topk_static(const dash_layer_params* p, const float* scores, int32_t n, int32_t keep_low,
+                                    uint8_t* halt_mask, int32_t* chunk_keep_counts, void* hip_stream) {
+    dash_status st = check_params(p);
+    if (st != DASH_OK) return st;
+    if (n < 0) return DASH_ERR_INVALID_ARG;
+    if (n > kStaticTopkMaxRows) return DASH_ERR_UNSUPPORTED;  // beyond what the static scratch holds
+    if (n == 0) return DASH_OK;
+    if (!scores || !halt_mask || !chunk_keep_counts) return DASH_ERR_INVALID_ARG;
+    if (p->k_keep < 0 && !(p->rho >= 0.0 && p->rho < 1.0)) return DASH_ERR_INVALID_ARG;
+    void* scratch = nullptr;
+    st = topk_static_scratch_ptr(&scratch);
+    if (st != DASH_OK) return st;
+    // the kernels write the selection state and every tie count they later read, so nothing has to be cleared
+    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, scratch, (hipStream_t)hip_stream);
 }
 
 dash_status dash_score_diff_rows(const void* x_new, const void* x_old, int32_t n, int32_t d, int32_t dtype,

@@ -67,6 +67,8 @@ dash_status launch_rmsnorm_qkv_fused(const dash_layer_params& p, const void* x, 
                                      void* k, void* v, void* h, void* split_ws, size_t split_bytes, hipStream_t s);
 // score_decide.hip
 size_t decide_workspace_bytes();
+constexpr int kStaticTopkMaxRows = 1 << 20;  // row limit of the allocation-free TopK entry point
+dash_status topk_static_scratch_ptr(void** out);  // this device's copy of its file-scope scratch array
 dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,
                                 float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
                                 hipStream_t s);

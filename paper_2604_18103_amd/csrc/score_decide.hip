@@ -4,6 +4,8 @@
 // Scores are finished here from per-row partial sums of squares that the projection stage took from
 // its fp32 accumulators: partials [P, n, 2] = (sum delta^2, sum x^2), summed over P in a fixed order
 // so the result is bit-reproducible.
+#include <mutex>
+
 #include "common.h"
 
 namespace dash {
@@ -279,6 +281,34 @@ __global__ __launch_bounds__(256) void score_rows_kernel(const float* __restrict
 }
 
 size_t decide_workspace_bytes() { return 256; }
+
+// ------------------------------------------------------------------------------------------------
+// Scratch of the allocation-free TopK entry point (dash_decide_topk_static): the selection state and the tie
+// counts of up to kStaticTopkMaxRows rows live in this file-scope device array instead of a caller's workspace.
+// Every GPU the library runs on holds its own copy at its own address until the process ends. In host code the
+// array's name is only a stand-in for the symbol: the device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and that pointer is what the launches get.
+// ------------------------------------------------------------------------------------------------
+constexpr size_t kStaticTopkScratchBytes = 256 + sizeof(int32_t) * (size_t)(kStaticTopkMaxRows / kChunkRows);
+static __device__ __align__(256) unsigned char topk_static_scratch[kStaticTopkScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_topk_scratch_ptr[kMaxDevices];   // device address of topk_static_scratch, per device; nullptr = not asked yet
+static std::mutex g_topk_scratch_mutex;
+
+// Device address of the current device's copy of the scratch array (asked for on the first call on that device).
+dash_status topk_static_scratch_ptr(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DASH_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_topk_scratch_mutex);
+    if (!g_topk_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(topk_static_scratch)) != hipSuccess || !ptr) return DASH_ERR_HIP;
+        g_topk_scratch_ptr[dev] = ptr;
+    }
+    *out = g_topk_scratch_ptr[dev];
+    return DASH_OK;
+}
 
 dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,
                                 float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
