@@ -29,6 +29,49 @@ HBM_PEAK_GBS = 8000.0
 FLASH_TRAFFIC_BYTES = {"qwen_32k_half": 388e6 + 117e6}
 
 
+def measure_mfma_peak(seconds_per_case=0.25):
+    """What the matrix pipe sustains on this machine with nothing else running: the library's register-only MFMA loop
+    (dash_mfma_probe: no memory traffic, 8 waves per compute unit) in the two instruction shapes the kernels use,
+    on zero operands (the published peak's conditions) and on N(0,1) operands (the workloads' data: the part
+    lowers its clock under the power the operand bits draw). TFLOP/s per case, each from one launch of about
+    `seconds_per_case` timed with events on the launch stream."""
+    import torch
+    from paper_2604_18103_amd import binding as B
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty((cus * 512,), dtype=torch.float32, device="cuda")
+    out = {}
+    for shape, sname in ((0, "32x32x16"), (1, "16x16x32")):
+        for normal, dname in ((False, "zeros"), (True, "normal")):
+            B.dash_mfma_probe(shape, normal, 20000, cus, sink)          # warm-up, and a first rate estimate
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flops = B.dash_mfma_probe(shape, normal, 20000, cus, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            rate = flops / (e0.elapsed_time(e1) * 1e-3)
+            iters = max(20000, min(4000000, int(20000 * seconds_per_case * rate / flops)))
+            e0.record()
+            flops = B.dash_mfma_probe(shape, normal, iters, cus, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            out[f"{sname}_{dname}"] = flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    return out
+
+
+def run_mfma_peak_bench(args):
+    """`--workload mfma_peak`: the probe alone, one second per case."""
+    peak = measure_mfma_peak(1.0)
+    best = peak["32x32x16_zeros"]
+    print(json.dumps({
+        "metric": "sustained bf16 MFMA rate of a register-only loop (32x32x16, zero operands)",
+        "value": best, "unit": "TFLOP/s", "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "mfma_peak"},
+        "roofline": {"bound": "mfma", "achieved": best, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": best / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+        "measured_peak_tflops": peak}))
+
+
 def attention_flops(cfg, n):
     pairs = n * (n + 1) / 2 if cfg.causal else n * n
     return 4.0 * cfg.head_dim * cfg.n_q_heads * pairs
@@ -59,7 +102,8 @@ def cpu_baseline(cfg, L, rows_target=3072):
     ref.attn_layer(L["x"], L["q"], L["k"], L["v"], L["w_o"], L["active_idx"], causal=cfg.causal, rows=rows)
     dt = time.perf_counter() - t0
     return {"value": len(rows) / dt, "unit": "active tokens/s", "cores": ref.num_threads(), "kind": "oracle",
-            "sample": f"{len(rows)} uniformly sampled query rows of the same workload against all "
+            "sampled": True,
+            "sample": f"SAMPLED, not the full configuration: {len(rows)} uniformly sampled query rows of the same workload against all "
                       f"{n} keys/values, full layer per row, {dt:.1f} s; tokens/s = rows / seconds"}
 
 
@@ -344,8 +388,8 @@ def main():
                     help="a key of paper_2604_18103_amd.inputs.CONFIGS (single-layer workloads; qwen_32k_chain is "
                          "the 8-layer chain), qwen_32k_single_shot (28 full blocks, one halting decision), "
                          "qwen_32k_multi_shot (1- to 4-shot schedules under one budget) or qwen_vl_8k_extreme "
-                         "(one shot, 75 % to 99 % of the tokens halted), or aux_kernels (the bandwidth-bound kernels "
-                         "beside the layer, one by one)")
+                         "(one shot, 75 % to 99 % of the tokens halted), aux_kernels (the bandwidth-bound kernels "
+                         "beside the layer, one by one) or mfma_peak (the register-only MFMA probe alone)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run device-to-device copies of this many MiB (a plain copy kernel of known "
@@ -367,6 +411,9 @@ def main():
     B.lib()  # fail loudly if the HIP library is missing
     if args.workload == "qwen_32k_single_shot":
         run_single_shot_bench(args, I.CONFIGS["qwen_32k_chain"])
+        return
+    if args.workload == "mfma_peak":
+        run_mfma_peak_bench(args)
         return
     if args.workload == "aux_kernels":
         run_aux_kernels_bench(args, I.CONFIGS["qwen_32k_half"])
@@ -454,6 +501,7 @@ def main():
     sc_bytes = score_compact_bytes(cfg, n, n_kept, B.norm_partials_per_row(p), elem)
     sc_gbs = sc_bytes / ((mean_ms[2] + mean_ms[3]) * 1e-3) / 1e9
 
+    peak = measure_mfma_peak()        # after the timed region: what the matrix pipe sustains on this machine
     out = {
         "metric": "active tokens/s, one DASH attention layer step (attention + W_o/residual + score/halting "
                   "+ compaction), Qwen2.5-7B-shaped layer" if args.workload.startswith("qwen")
@@ -470,12 +518,20 @@ def main():
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": fa_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": FLASH_TRAFFIC_BYTES.get(cfg.name),
+                     "traffic_source": "offline constant: rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE runs of this "
+                                       "command, scaled by a copy of known size (profiles/); not measured in this run",
                      "algorithmic_flops_per_launch": attention_flops(cfg, n),
-                     "kernel_ms": float(mean_ms[0])},
+                     "kernel_ms": float(mean_ms[0]),
+                     "measured_peak": peak,
+                     "measured_peak_note": "TFLOP/s of a register-only MFMA loop on this box, measured in this run: "
+                                           "zero operands reach the published peak, N(0,1) operands (the workload's "
+                                           "data) hold the part at its power limit",
+                     "frac_of_measured_peak_on_normal_data": fa_tflops / peak["32x32x16_normal"]},
         "stages_ms": dict(zip(B.STAGE_NAMES, [float(v) for v in mean_ms])),
         "roofline_wo": {"kernel": "gemm_mfma_kernel", "bound": "mfma", "achieved": wo_tflops,
                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": wo_tflops / MFMA_BF16_PEAK_TFLOPS},
+                        "frac": wo_tflops / MFMA_BF16_PEAK_TFLOPS,
+                        "frac_of_measured_peak_on_normal_data": wo_tflops / peak["16x16x32_normal"]},
         "roofline_attn_plus_wo": {"bound": "mfma", "achieved": both_tflops, "peak": MFMA_BF16_PEAK_TFLOPS,
                                   "unit": "TFLOP/s", "frac": both_tflops / MFMA_BF16_PEAK_TFLOPS},
         "roofline_score_compact": {"bound": "hbm", "achieved": sc_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -247,6 +247,17 @@ dash_status dash_scatter_rows(const void *rows, const int32_t *idx, const uint8_
 dash_status dash_validate_active_idx(const int32_t *active_idx, int32_t n, int32_t N, int32_t *violations,
                                      void *hip_stream);
 
+/* Measurement aid (no step of the method): a register-only loop of independent bf16 MFMAs, 8 waves per workgroup,
+ * no memory or LDS traffic, to read what the matrix pipe sustains on this part beside the published peak.
+ * shape 0: v_mfma_f32_32x32x16_bf16 (the attention kernel's), 1: v_mfma_f32_16x16x32_bf16 (the GEMMs');
+ * normal_data 0: all operands zero, else N(0,1) values as in the workloads (the part lowers its clock under the
+ * power the operand bits draw). Runs `iters` iterations in each of `workgroups` workgroups (use the number of
+ * compute units); sink: device fp32 [workgroups * 512], written once at the end. The caller times the launch;
+ * dash_mfma_probe_flops(iters, workgroups) is the flop count of one launch. */
+dash_status dash_mfma_probe(int32_t shape, int32_t normal_data, int32_t iters, int32_t workgroups, float *sink,
+                            void *hip_stream);
+double dash_mfma_probe_flops(int32_t iters, int32_t workgroups);
+
 /* Host arithmetic: tokens kept out of n.
  * paper_impl_rounding == 0: floor((1 - rho) n) (Eq. 3), evaluated as n - ceil(rho n) with a product that lies
  * within 1e-9 (relative) of a whole number taken as that number, so that decimal ratios give what exact

@@ -94,6 +94,10 @@ def lib() -> C.CDLL:
     L.dash_validate_active_idx.argtypes = [_vp, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_score_diff_rows.argtypes = [_vp, _vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
     L.dash_decide_topk.argtypes = [pp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp, C.c_size_t, _vp]
+    L.dash_mfma_probe.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, _vp]
+    L.dash_mfma_probe.restype = C.c_int
+    L.dash_mfma_probe_flops.argtypes = [C.c_int32, C.c_int32]
+    L.dash_mfma_probe_flops.restype = C.c_double
     L.dash_decide_topk_static.argtypes = [pp, _vp, C.c_int32, C.c_int32, _vp, _vp, _vp]
     L.dash_decide_topk_static.restype = C.c_int
     L.dash_ffn_workspace_bytes.restype = C.c_size_t
@@ -300,6 +304,13 @@ def dash_decide_topk(params, scores, n, keep_low, halt_mask, chunk_keep_counts, 
     _check(lib().dash_decide_topk(C.byref(params), _p(scores), int(n), int(bool(keep_low)), _p(halt_mask),
                                   _p(chunk_keep_counts), _p(workspace), workspace.numel(), _stream()),
            "dash_decide_topk")
+
+
+def dash_mfma_probe(shape: int, normal_data: bool, iters: int, workgroups: int, sink) -> float:
+    """Enqueue the register-only MFMA loop (measurement aid); returns the flops of the launch."""
+    _check(lib().dash_mfma_probe(int(shape), int(bool(normal_data)), int(iters), int(workgroups), _p(sink), _stream()),
+           "dash_mfma_probe")
+    return float(lib().dash_mfma_probe_flops(int(iters), int(workgroups)))
 
 
 TOPK_STATIC_MAX_ROWS = 1 << 20

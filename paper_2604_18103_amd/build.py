@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libdash.so")
 CHECK_LIB = os.path.join(HERE, "libdash_staging_check.so")  # host-only: CPU check of the kernels' staging addresses
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "flash_fwd.hip", "wo_gemm.hip", "rope.hip", "score_decide.hip", "compact.hip"]
+SOURCES = ["api.hip", "flash_fwd.hip", "wo_gemm.hip", "rope.hip", "score_decide.hip", "compact.hip", "mfma_probe.hip"]
 
 # packed fp32 instructions are kept off on this target
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

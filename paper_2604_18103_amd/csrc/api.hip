@@ -408,6 +408,18 @@ dash_status dash_rope_qk(const dash_layer_params* p, void* q, void* k, const int
     return launch_rope_qk(*p, q, k, active_idx, n, theta_base, (hipStream_t)hip_stream);
 }
 
+double dash_mfma_probe_flops(int32_t iters, int32_t workgroups) {
+    if (iters <= 0 || workgroups <= 0) return 0.0;
+    return 524288.0 * (double)iters * 8.0 * (double)workgroups;  // per iteration and wave, 8 waves per workgroup
+}
+
+dash_status dash_mfma_probe(int32_t shape, int32_t normal_data, int32_t iters, int32_t workgroups, float* sink,
+                            void* hip_stream) {
+    if ((shape != 0 && shape != 1) || iters <= 0 || workgroups <= 0 || workgroups > 65536 || !sink)
+        return DASH_ERR_INVALID_ARG;
+    return launch_mfma_probe(shape == 0, normal_data != 0, iters, workgroups, sink, (hipStream_t)hip_stream);
+}
+
 dash_status dash_validate_active_idx(const int32_t* active_idx, int32_t n, int32_t N, int32_t* violations,
                                      void* hip_stream) {
     if (n < 0 || !violations || (n > 0 && !active_idx)) return DASH_ERR_INVALID_ARG;

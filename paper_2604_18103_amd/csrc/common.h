@@ -90,6 +90,9 @@ dash_status launch_score_diff_rows(const void* x_new, const void* x_old, int n, 
                                    float* scores, hipStream_t s);
 dash_status launch_rope_qk(const dash_layer_params& p, void* q, void* k, const int32_t* active_idx, int n,
                            double theta, hipStream_t s);
+// mfma_probe.hip
+constexpr int kProbeThreadsPerGroup = 512;
+dash_status launch_mfma_probe(int wide, int normal_data, int iters, int workgroups, float* sink, hipStream_t s);
 dash_status launch_validate_idx(const int32_t* idx, int n, int N, int32_t* violations, hipStream_t s);
 
 }  // namespace dash

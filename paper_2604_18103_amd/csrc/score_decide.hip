@@ -94,119 +94,145 @@ __device__ __forceinline__ uint32_t rank_key(float f, int keep_low) {
 struct TopkState {
     uint32_t threshold_key;  // key of the K-th largest candidate score
     int32_t tie_quota;       // how many rows with exactly that key are kept (earliest rows first)
+    int32_t ties_ranked;     // 0: every row with that key is kept (no per-chunk tie counts were written)
 };
 
 constexpr int kSelectThreads = 1024;
+constexpr int kSelectBins = 2048;   // histogram bins of one radix pass (11-bit digits)
+constexpr int kSelectBatch = 16;    // scores a thread has in flight per load batch
 
-// TopK selection (Eq. 3): one workgroup finds the key of the k_cand-th largest score among the
-// unprotected rows by four 8-bit radix passes (integer histograms in LDS), then counts, per 64-row
-// chunk, the rows that tie with it, so the flag kernel can keep the earliest ties first.
+// TopK selection (Eq. 3): one workgroup finds the key of the k_cand-th largest score among the unprotected rows by
+// three radix passes over the order-preserving keys (digits of 11, 11 and 10 bits, integer histograms in LDS: the
+// order of the adds does not matter, so the result is exact and reproducible). A pass streams the scores with 16
+// independent loads per thread in flight, so its time is a few memory latencies, not one per 1024 rows. When more
+// rows tie with the K-th key than may be kept, it also counts those ties per 64-row chunk, so the flag kernel can
+// keep the earliest ones; with distinct scores (the usual case) that pass over the scores is skipped.
 __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, int keep_low,
     TopkState* __restrict__ st, int32_t* __restrict__ tie_counts) {
-    __shared__ int hist[256], hist_suf[256], wave_tot[4];
-    __shared__ uint32_t sh_prefix, sh_prefix_next;
-    __shared__ int sh_remaining, sh_remaining_next;
+    __shared__ int hist[kSelectBins];
+    __shared__ int wave_tot[kSelectThreads / kWave];
+    __shared__ uint32_t sh_prefix;
+    __shared__ int sh_remaining, sh_ties;
     const int tid = threadIdx.x;
+    const int lane = tid % kWave, wave = tid / kWave;
     const int lo = min(n_first, n), hi = max(lo, n - n_last);  // candidates are rows [lo, hi)
     const int n_cand = hi - lo;
     const int n_prot = n - n_cand;
     int k_cand = k_keep - n_prot;
     k_cand = max(0, min(k_cand, n_cand));
-    if (tid == 0) {
-        sh_prefix = 0u;
-        sh_remaining = k_cand;
-    }
     if (k_cand == 0) {
-        // nothing unprotected survives
+        // nothing unprotected survives: no key exceeds the threshold and no tie is kept
         if (tid == 0) {
             st->threshold_key = 0xFFFFFFFFu;
             st->tie_quota = 0;
+            st->ties_ranked = 0;
         }
-        const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
-        for (int c = tid; c < n_chunks; c += kSelectThreads) tie_counts[c] = 0;
         return;
     }
-    const int lane_s = tid % kWave, wave_s = tid / kWave;
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        for (int b = tid; b < 256; b += kSelectThreads) hist[b] = 0;
+    uint32_t prefix = 0u;      // digits found so far (in place), uniform
+    int remaining = k_cand;    // rank of the wanted key among the keys that share the prefix, uniform
+#pragma unroll 1
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
+        const uint32_t digit_mask = pass == 2 ? 0x3FFu : 0x7FFu;
+        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
+        for (int b = tid; b < kSelectBins; b += kSelectThreads) hist[b] = 0;
         __syncthreads();
-        const uint32_t prefix = sh_prefix;
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int r0 = lo; r0 < hi; r0 += kSelectThreads) {
-            const int r = r0 + tid;
-            uint32_t bin = 0;
-            bool mine = false;
-            if (r < hi) {
-                const uint32_t key = rank_key(scores[r], keep_low);
-                mine = (key & hi_mask) == prefix;
-                bin = (key >> shift) & 0xFFu;
-            }
-            // Scores of one layer share a few exponents, so most lanes of a wave hit the same one or two
-            // bins in the first pass: those are counted with one ballot and one add per bin, the rest add
-            // on their own (integer adds: the order does not matter).
+        for (int r0 = lo; r0 < hi; r0 += kSelectThreads * kSelectBatch) {
+            float v[kSelectBatch];
 #pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const unsigned long long todo = __ballot(mine);
-                if (todo == 0ull) break;
-                const int leader = __ffsll((long long)todo) - 1;
-                const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
-                const unsigned long long same = __ballot(mine && bin == lb);
-                if (lane_s == leader) atomicAdd(&hist[lb], (int)__popcll(same));
-                if (bin == lb) mine = false;
+            for (int u = 0; u < kSelectBatch; ++u) {
+                const int r = r0 + u * kSelectThreads + tid;
+                v[u] = r < hi ? scores[r] : 0.f;
             }
-            if (mine) atomicAdd(&hist[bin], 1);
+#pragma unroll
+            for (int u = 0; u < kSelectBatch; ++u) {
+                const int r = r0 + u * kSelectThreads + tid;
+                const uint32_t key = rank_key(v[u], keep_low);
+                bool mine = r < hi && (key & hi_mask) == prefix;
+                const uint32_t bin = (key >> shift) & digit_mask;
+                // Scores of one layer share a few exponents, so most lanes of a wave hit the same one or two bins
+                // in the first pass: those are counted with one ballot and one add per bin, the rest add on their own.
+                if (pass == 0) {
+#pragma unroll
+                    for (int it = 0; it < 2; ++it) {
+                        const unsigned long long todo = __ballot(mine);
+                        if (todo == 0ull) break;
+                        const int leader = __ffsll((long long)todo) - 1;
+                        const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
+                        const unsigned long long same = __ballot(mine && bin == lb);
+                        if (lane == leader) atomicAdd(&hist[lb], (int)__popcll(same));
+                        if (bin == lb) mine = false;
+                    }
+                }
+                if (mine) atomicAdd(&hist[bin], 1);
+            }
         }
         __syncthreads();
         // The bin that holds the remaining-th largest key: the largest b with (keys in bins >= b) >= remaining.
-        // Suffix sums over the 256 bins by the first four waves (bin = thread), then the one thread whose bin
-        // crosses the count publishes the new prefix.
-        if (tid < 256) {
-            const int v = hist[tid];
-            int suf = v;  // sum over bins tid .. end of this wave's 64 bins
+        // Thread t owns bins 2t and 2t + 1; suffix sums over the threads of a wave by shuffles, over the waves
+        // through LDS.
+        const int h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+        int suf = h0 + h1;  // becomes the count of keys in bins >= 2 tid
 #pragma unroll
-            for (int o = 1; o < kWave; o <<= 1) {
-                const int t = __shfl_down(suf, o);
-                if (lane_s + o < kWave) suf += t;
-            }
-            if (lane_s == 0) wave_tot[wave_s] = suf;
-            hist_suf[tid] = suf;
+        for (int o = 1; o < kWave; o <<= 1) {
+            const int t = __shfl_down(suf, o);
+            if (lane + o < kWave) suf += t;
+        }
+        if (lane == 0) wave_tot[wave] = suf;
+        __syncthreads();
+        for (int w = wave + 1; w < kSelectThreads / kWave; ++w) suf += wave_tot[w];
+        // exactly one bin satisfies excl < remaining <= incl (the keys under the prefix number at least `remaining`)
+        const int incl1 = suf - h0, excl1 = incl1 - h1;  // bin 2 tid + 1
+        const int incl0 = suf, excl0 = incl1;            // bin 2 tid
+        int found = -1, found_excl = 0, found_cnt = 0;
+        if (excl1 < remaining && remaining <= incl1) {
+            found = 2 * tid + 1;
+            found_excl = excl1;
+            found_cnt = h1;
+        } else if (excl0 < remaining && remaining <= incl0) {
+            found = 2 * tid;
+            found_excl = excl0;
+            found_cnt = h0;
+        }
+        if (found >= 0) {
+            sh_prefix = prefix | ((uint32_t)found << shift);
+            sh_remaining = remaining - found_excl;
+            sh_ties = found_cnt;  // after the last pass: rows whose key equals the threshold key
         }
         __syncthreads();
-        if (tid < 256) {
-            int incl = hist_suf[tid];
-            for (int w = wave_s + 1; w < 4; ++w) incl += wave_tot[w];
-            const int excl = incl - hist[tid];
-            const int remaining = sh_remaining;
-            // exactly one bin satisfies excl < remaining <= incl when the candidates under the prefix are at
-            // least `remaining` (they are); bin 0 also takes the (unreachable) case of too few
-            const bool crossing = excl < remaining && (remaining <= incl || tid == 0);
-            if (crossing) {
-                sh_prefix_next = prefix | ((uint32_t)tid << shift);
-                sh_remaining_next = remaining - excl;
-            }
-        }
-        __syncthreads();
-        if (tid == 0) {
-            sh_prefix = sh_prefix_next;
-            sh_remaining = sh_remaining_next;
-        }
-        __syncthreads();
+        prefix = sh_prefix;
+        remaining = sh_remaining;
+        // the next pass clears hist only after every thread has passed this barrier and read its bins
     }
-    const uint32_t T = sh_prefix;
+    const uint32_t T = prefix;
+    const int ties = sh_ties;
+    const bool rank_ties = ties > remaining;  // more rows tie with the K-th key than may be kept
     if (tid == 0) {
         st->threshold_key = T;
-        st->tie_quota = sh_remaining;  // >= 1: ties (key == T) still to be kept
+        st->tie_quota = remaining;  // >= 1: ties (key == T) still to be kept
+        st->ties_ranked = rank_ties ? 1 : 0;
     }
-    // ties per chunk, one wave per chunk
-    const int lane = tid % kWave, wave = tid / kWave;
+    if (!rank_ties) return;
+    // ties per chunk, one wave per chunk, four chunks in flight per wave
     const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
-    for (int c = wave; c < n_chunks; c += kSelectThreads / kWave) {
-        const int row = c * kChunkRows + lane;
-        const bool tie = row >= lo && row < hi && rank_key(scores[row], keep_low) == T;
-        const unsigned long long m = __ballot(tie);
-        if (lane == 0) tie_counts[c] = __popcll(m);
+    constexpr int kWaves = kSelectThreads / kWave;
+    for (int c0 = wave; c0 < n_chunks; c0 += 4 * kWaves) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int row = (c0 + u * kWaves) * kChunkRows + lane;
+            v[u] = row < hi ? scores[row] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * kWaves;
+            const int row = c * kChunkRows + lane;
+            const bool tie = row >= lo && row < hi && rank_key(v[u], keep_low) == T;
+            const unsigned long long m = __ballot(tie);
+            if (lane == 0 && c < n_chunks) tie_counts[c] = __popcll(m);
+        }
     }
 }
 
@@ -220,14 +246,18 @@ __global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict_
     __shared__ int wave_part[4];
     const int chunk = blockIdx.x;  // one workgroup per 64-row chunk; wave 0 decides
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    int part = 0;
-    for (int c = tid; c < chunk; c += 256) part += tie_counts[c];
+    const bool ranked = st->ties_ranked != 0;  // uniform
+    int tie_base = 0;
+    if (ranked) {
+        int part = 0;
+        for (int c = tid; c < chunk; c += 256) part += tie_counts[c];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
-    if (lane == 0) wave_part[wave] = part;
-    __syncthreads();
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o);
+        if (lane == 0) wave_part[wave] = part;
+        __syncthreads();
+        tie_base = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
+    }
     if (wave != 0) return;
-    const int tie_base = wave_part[0] + wave_part[1] + wave_part[2] + wave_part[3];
     const uint32_t T = st->threshold_key;
     const int quota = st->tie_quota;
     const int row = chunk * kChunkRows + lane;
@@ -242,7 +272,8 @@ __global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict_
         }
     }
     const unsigned long long tie_mask = __ballot(tie);
-    if (tie) keep = tie_base + __popcll(tie_mask & ((1ull << lane) - 1ull)) < quota;
+    // unranked: every tie is kept when any is (quota 0 only with the all-halt state, where no key is kept)
+    if (tie) keep = ranked ? tie_base + __popcll(tie_mask & ((1ull << lane) - 1ull)) < quota : quota > 0;
     if (row < n) halt[row] = keep ? 0 : 1;
     const unsigned long long m = __ballot(keep);
     if (lane == 0) chunk_counts[chunk] = __popcll(m);
