@@ -64,13 +64,45 @@ inline int splitk_parts(int tiles, int ksteps, int cu) {
     return s < 2 ? 1 : s;
 }
 
+// Order in which the output tiles of a product are handed out ("tile index" below), and which workgroup takes which
+// index. Workgroup b of a launch runs on XCD b % 8, and each XCD has its own L2: what the 32 workgroups that an XCD
+// runs at one time share in that L2 is decided here.
+//  - row tiles a multiple of 8 ("plain"): tile index = column-major position (row tile fastest), workgroup b takes
+//    index b. An XCD then holds row tiles b % 8, b % 8 + 8, ... of four consecutive tile columns: 8 A panels and
+//    4 B panels for 32 tiles, and all XCDs are in the same four tile columns at the same time.
+//  - otherwise: column panels of 4 tile columns (the last one narrower), row by row inside a panel, so that 32
+//    consecutive indices are a block of 8 x 4 tiles; the indices are dealt to the XCDs as 8 contiguous stretches
+//    (workgroup b takes index (b % 8) * seg + b / 8), equally many per XCD. With the plain order a row-tile count
+//    that is not a multiple of 8 would scatter an XCD's 32 tiles over up to 32 row panels.
+constexpr int kGPanel = 4;
+DASH_HD void gemm_tile_of(int idx, int mt, int nt, bool plain, int& tile_m, int& tile_n) {
+    if (plain) {
+        tile_m = idx % mt;
+        tile_n = idx / mt;
+        return;
+    }
+    const int per_panel = mt * kGPanel, whole = nt / kGPanel;
+    const int p = idx / per_panel;
+    if (p < whole) {
+        const int r = idx - p * per_panel;
+        tile_m = r / kGPanel;
+        tile_n = p * kGPanel + r % kGPanel;
+    } else {
+        const int w = nt - whole * kGPanel;  // >= 1: idx < mt * nt
+        const int r = idx - whole * per_panel;
+        tile_m = r / w;
+        tile_n = whole * kGPanel + r % w;
+    }
+}
+
 // How launch_gemm cuts a product into launches: either `parts` >= 2 split-K parts over all tiles, or `full`
-// 256-row tiles followed by `rest` tiles run as 128-row half tiles (when the tiles left over after the whole
-// rounds would occupy at most half of the units).
+// 256-row tiles (a grid of `grid` workgroups: gemm_index_of) followed by `rest` tiles run as 128-row half tiles
+// (when the tiles left over after the whole rounds would occupy at most half of the units).
 struct GemmPlan {
     int mt, nt, tiles, ksteps;
     int parts, ksteps_per_part;  // parts >= 2: split-K launch
     int full, rest;              // otherwise
+    int plain, seg, grid;        // tile order of the whole tiles, indices per XCD, workgroups of their launch
 };
 inline GemmPlan gemm_plan(int M, int K, int N, int cu, bool may_split, size_t split_bytes) {
     GemmPlan g{};
@@ -80,6 +112,7 @@ inline GemmPlan gemm_plan(int M, int K, int N, int cu, bool may_split, size_t sp
     g.ksteps = K / kGK;
     g.parts = 1;
     g.ksteps_per_part = g.ksteps;
+    g.plain = g.mt % 8 == 0 ? 1 : 0;
     if (may_split) {
         int parts = splitk_parts(g.tiles, g.ksteps, cu);
         const size_t per_part = (size_t)M * N * sizeof(float);
@@ -94,7 +127,16 @@ inline GemmPlan gemm_plan(int M, int K, int N, int cu, bool may_split, size_t sp
     g.rest = cu > 0 ? g.tiles % cu : 0;
     if (2 * g.rest > cu) g.rest = 0;
     g.full = g.tiles - g.rest;
+    g.seg = (g.full + 7) / 8;
+    g.grid = g.plain ? g.full : 8 * g.seg;
     return g;
+}
+
+// Tile index that workgroup b of the whole-tile launch takes, or -1 (padding of the last stretch: the workgroup leaves).
+DASH_HD int gemm_index_of(int b, int full, bool plain, int seg) {
+    if (plain) return b;
+    const int idx = (b % 8) * seg + b / 8;
+    return (b / 8 < seg && idx < sa_min(((b % 8) + 1) * seg, full)) ? idx : -1;
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -5,6 +5,8 @@
 // the operand the lane is meant to fetch. A wrapped offset, a wrong clamp or a load outside the operand fails.
 #include <stdint.h>
 
+#include <vector>
+
 #include "staging_addr.h"
 
 using namespace dash;
@@ -66,19 +68,37 @@ bool sampled(int idx, int count, bool all) { return all || idx == 0 || idx == co
 
 extern "C" {
 
-// Checks every staging load of the launches that the library makes for C[M,N] = A[M,K] B[K,N] on `cu` compute
-// units (split_bytes > 0: scratch for split-K is available). Products with more than 4096 tiles are checked on
-// the first and last row and column tiles of every launch (the addresses are affine in the tile indices).
-// Returns 0 when all loads are right; *n_loads = loads checked.
+// Checks the launches that the library makes for C[M,N] = A[M,K] B[K,N] on `cu` compute units (split_bytes > 0:
+// scratch for split-K is available): that the tile order visits every tile once, that the workgroups of the
+// whole-tile launch take every whole tile exactly once, equally many per XCD (workgroup b runs on XCD b % 8), and
+// every staging load. Products with more than 4096 tiles have their loads checked on the first and last row and
+// column tiles only (the addresses are affine in the tile indices); the coverage is always checked in full.
+// Returns 0 when everything is right; *n_loads = loads checked.
 int dash_check_gemm_staging(int M, int K, int N, int cu, unsigned long long split_bytes, long long* n_loads) {
     Counter c;
     if (M <= 0 || K <= 0 || K % kGK != 0 || N <= 0 || N % 8 != 0) return -1;
     const GemmPlan g = gemm_plan(M, K, N, cu, split_bytes > 0, (size_t)split_bytes);
     const bool all = g.tiles <= 4096;
+    const bool plain = g.plain != 0;
+    // the tile order is a bijection onto the tile grid
+    {
+        std::vector<char> seen((size_t)g.tiles, 0);
+        for (int idx = 0; idx < g.tiles; ++idx) {
+            int tm = -1, tn = -1;
+            gemm_tile_of(idx, g.mt, g.nt, plain, tm, tn);
+            if (tm < 0 || tm >= g.mt || tn < 0 || tn >= g.nt || seen[(size_t)tn * g.mt + tm]) {
+                c.fail(9);
+                break;
+            }
+            seen[(size_t)tn * g.mt + tm] = 1;
+        }
+    }
+    auto loads_wanted = [&](int tm, int tn) { return sampled(tm, g.mt, all) || sampled(tn, g.nt, all); };
     if (g.parts >= 2) {
         for (int tile = 0; tile < g.tiles; ++tile) {
-            const int tm = tile % g.mt, tn = tile / g.mt;
-            if (!(sampled(tm, g.mt, all) || sampled(tn, g.nt, all))) continue;
+            int tm, tn;
+            gemm_tile_of(tile, g.mt, g.nt, plain, tm, tn);
+            if (!loads_wanted(tm, tn)) continue;
             for (int part = 0; part < g.parts; ++part) {
                 const int ks0 = part * g.ksteps_per_part;
                 const int nk = sa_min(g.ksteps_per_part, g.ksteps - ks0);
@@ -88,25 +108,43 @@ int dash_check_gemm_staging(int M, int K, int N, int cu, unsigned long long spli
         }
     } else {
         if (g.full + g.rest != g.tiles || g.full < 0 || g.rest < 0) c.fail(8);
-        for (int tile = 0; tile < g.full; ++tile) {
-            const int tm = tile % g.mt, tn = tile / g.mt;
-            if (!(sampled(tm, g.mt, all) || sampled(tn, g.nt, all) || tile == g.full - 1)) continue;
-            check_gemm_workgroup(M, K, N, 4, tm, tn, 0, 0, g.ksteps, c);
+        if (g.full > 0 && (g.grid < g.full || g.grid > g.full + 15)) c.fail(10);
+        std::vector<int> taken((size_t)g.tiles, 0);
+        int per_xcd[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int b = 0; b < (g.full > 0 ? g.grid : 0); ++b) {
+            const int idx = gemm_index_of(b, g.full, plain, g.seg);
+            if (idx < 0) continue;
+            if (idx >= g.full) {
+                c.fail(11);
+                continue;
+            }
+            ++taken[(size_t)idx];
+            ++per_xcd[b % 8];
+            int tm, tn;
+            gemm_tile_of(idx, g.mt, g.nt, plain, tm, tn);
+            if (loads_wanted(tm, tn) || idx == g.full - 1) check_gemm_workgroup(M, K, N, 4, tm, tn, 0, 0, g.ksteps, c);
         }
+        for (int t = 0; t < g.full; ++t)
+            if (taken[(size_t)t] != 1) c.fail(12);
+        for (int x = 0; x < 8; ++x)  // no XCD has more than a stretch's worth, none is short by more than the padding
+            if (per_xcd[x] > (g.full + 7) / 8 || per_xcd[x] + 8 < g.full / 8) c.fail(13);
         for (int b = 0; b < 2 * g.rest; ++b) {  // half tiles: workgroup b handles half b % 2 of tile full + b / 2
-            const int tile = g.full + b / 2;
-            check_gemm_workgroup(M, K, N, 2, tile % g.mt, tile / g.mt, b % 2, 0, g.ksteps, c);
+            int tm, tn;
+            gemm_tile_of(g.full + b / 2, g.mt, g.nt, plain, tm, tn);
+            check_gemm_workgroup(M, K, N, 2, tm, tn, b % 2, 0, g.ksteps, c);
         }
     }
     if (n_loads) *n_loads = c.loads;
     return c.status;
 }
 
-// The launch decomposition of a product as launch_gemm makes it: out[0..5] = tiles, K steps, parts (>= 2: split-K),
-// K steps per part, whole 256-row tiles, tiles run as 128-row half tiles.
+// The launch decomposition of a product as launch_gemm makes it: out[0..7] = tiles, K steps, parts (>= 2: split-K),
+// K steps per part, whole 256-row tiles, tiles run as 128-row half tiles, plain tile order (1) or column panels
+// dealt to the XCDs in stretches (0), workgroups of the whole-tile launch.
 void dash_gemm_launch_plan(int M, int K, int N, int cu, unsigned long long split_bytes, int* out) {
     const GemmPlan g = gemm_plan(M, K, N, cu, split_bytes > 0, (size_t)split_bytes);
-    out[0] = g.tiles; out[1] = g.ksteps; out[2] = g.parts; out[3] = g.ksteps_per_part; out[4] = g.full; out[5] = g.rest;
+    out[0] = g.tiles; out[1] = g.ksteps; out[2] = g.parts; out[3] = g.ksteps_per_part; out[4] = g.full;
+    out[5] = g.rest; out[6] = g.plain; out[7] = g.grid;
 }
 
 // Checks every K and V staging load of the attention launch over n rows (K, V: [n][Hkv][DH] bf16): for each

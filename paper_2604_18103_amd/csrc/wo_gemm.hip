@@ -159,10 +159,18 @@ __device__ __forceinline__ __bf16* qkv_dst(__bf16* q, const QkvOut& o, int row, 
     return o.v + (size_t)row * o.Dkv + (col - o.Dkv);
 }
 
+// How the workgroups of a launch map to tiles (staging_addr.h: GemmPlan, gemm_index_of, gemm_tile_of).
+struct GemmLaunch {
+    int mt, nt, ksteps;
+    int full, plain, seg;   // the launch of 256-row tiles (MB = 4): tile order and indices per XCD
+    int first_tile;         // MB = 2: half tiles start at this tile index
+    int ksteps_per_split;   // EPI_SPLITK: K steps per part (part = blockIdx.y)
+};
+
 // MB = 32-row blocks per wave: 4 gives the 256-row tile, 2 a 128-row half tile. Half tiles finish the
 // grid: when the 256-row tiles do not fill a whole number of rounds over the compute units, the tiles of
-// the last, partly filled round are cut in two so that twice as many units share them.
-// Workgroup b handles tile first_tile + b (MB = 4) or half b % 2 of tile first_tile + b / 2 (MB = 2).
+// the last, partly filled round are cut in two so that twice as many units share them: workgroup b of that
+// second launch handles half b % 2 of tile first_tile + b / 2.
 template <int EPI, int MB>
 __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* __restrict__ A,
                                                                  const __bf16* __restrict__ B, int M, int K,
@@ -170,8 +178,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                                                                  __bf16* __restrict__ out,  // x_next or C
                                                                  float* __restrict__ partials,
                                                                  float* __restrict__ f32_out,  // delta (debug) or split sums
-                                                                 int n_mtiles, int first_tile,
-                                                                 int ksteps_per_split, QkvOut qkv) {
+                                                                 GemmLaunch L, QkvOut qkv) {
     constexpr int BM = 64 * MB;   // rows of this workgroup's tile
     constexpr int WM = 32 * MB;   // rows of a wave's tile
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
@@ -179,9 +186,20 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int wm = wave / 4, wn = wave % 4;
-    // consecutive workgroups walk down M inside one column tile, so the B panel stays hot in L2
-    const int tile = first_tile + (MB == 4 ? (int)blockIdx.x : (int)blockIdx.x / 2);
-    const int tile_m = tile % n_mtiles, tile_n = tile / n_mtiles;
+    // this workgroup's tile and K steps
+    int tile_idx, ks0 = 0, n_ksteps = L.ksteps;
+    if (EPI == EPI_SPLITK) {
+        tile_idx = (int)blockIdx.x;
+        ks0 = (int)blockIdx.y * L.ksteps_per_split;
+        n_ksteps = min(L.ksteps_per_split, L.ksteps - ks0);
+    } else if (MB == 2) {
+        tile_idx = L.first_tile + (int)blockIdx.x / 2;
+    } else {
+        tile_idx = gemm_index_of((int)blockIdx.x, L.full, L.plain != 0, L.seg);
+        if (tile_idx < 0) return;  // padding of the last stretch: the whole workgroup leaves
+    }
+    int tile_m, tile_n;
+    gemm_tile_of(tile_idx, L.mt, L.nt, L.plain != 0, tile_m, tile_n);
     const int m0 = tile_m * kGM + (MB == 4 ? 0 : ((int)blockIdx.x % 2) * BM), n0 = tile_n * kGN;
 
     constexpr int RB = 2 * MB;  // 16-row blocks of the wave's tile; 4 column blocks of 16
@@ -192,10 +210,6 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[a][b][r] = 0.f;
-
-    // K steps of this workgroup: all of them, or those of split blockIdx.y
-    const int ks0 = (int)blockIdx.y * ksteps_per_split;
-    const int n_ksteps = min(ksteps_per_split, K / kGK - ks0);
 
     // Staging. A tile: BM rows of 128 bytes, one load instruction = 8 rows; B tile: 64 rows of 512 bytes,
     // one instruction = 2 rows. Lane l lands in physical chunk l % (chunks per row) of its row and therefore
@@ -633,9 +647,10 @@ size_t gemm_splitk_bytes(int M_cap, int K, int N) {
     return (best + 255) / 256 * 256;
 }
 
-// 256x256 tiles for every whole round over the compute units; if the tiles left over would occupy at most
-// half of the units, they are run as 128-row half tiles by a second launch (same kernel, MB = 2). Products with
-// few tiles are split along K when `split_ws` (device scratch of `split_bytes`) allows.
+// 256x256 tiles for every whole round over the compute units, in an order that keeps the tiles an XCD runs at one
+// time close together (GemmPlan); if the tiles left over would occupy at most half of the units, they are run as
+// 128-row half tiles by a second launch (same kernel, MB = 2). Products with few tiles are split along K when
+// `split_ws` (device scratch of `split_bytes`) allows.
 template <int EPI>
 static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
                                __bf16* out, float* partials, float* delta_dbg, void* split_ws, size_t split_bytes,
@@ -644,22 +659,32 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
     // the staging loads address a tile with 32-bit lane offsets: 256 rows of A, 64 rows of B
     if ((size_t)kGM * K * 2 >= ((size_t)1 << 32) || (size_t)kGK * N * 2 + 2 * kGN >= ((size_t)1 << 32)) return DASH_ERR_UNSUPPORTED;
     const GemmPlan g = gemm_plan(M, K, N, compute_units(), split_ws != nullptr && !delta_dbg, split_bytes);
+    GemmLaunch L{};
+    L.mt = g.mt;
+    L.nt = g.nt;
+    L.ksteps = g.ksteps;
+    L.plain = g.plain;
     if (g.parts >= 2) {
         float* sums = reinterpret_cast<float*>(split_ws);
+        L.ksteps_per_split = g.ksteps_per_part;
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(g.tiles, g.parts), dim3(kGThreads), kGemmSmemBytes, s,
-                           A, B, M, K, N, nullptr, nullptr, nullptr, sums, g.mt, 0, g.ksteps_per_part, qkv);
+                           A, B, M, K, N, nullptr, nullptr, nullptr, sums, L, qkv);
         const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
         const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
         hipLaunchKernelGGL((splitk_reduce_kernel<EPI>), dim3((unsigned)((waves * kWave + 255) / 256)), dim3(256), 0,
                            s, sums, g.parts, M, N, x, out, partials, qkv);
         return launch_status();
     }
+    L.full = g.full;
+    L.seg = g.seg;
     if (g.full > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(g.full), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
-                           out, partials, delta_dbg, g.mt, 0, g.ksteps, qkv);
-    if (g.rest > 0)
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(g.grid), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
+                           out, partials, delta_dbg, L, qkv);
+    if (g.rest > 0) {
+        L.first_tile = g.full;
         hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * g.rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
-                           x, out, partials, delta_dbg, g.mt, g.full, g.ksteps, qkv);
+                           x, out, partials, delta_dbg, L, qkv);
+    }
     return launch_status();
 }
 

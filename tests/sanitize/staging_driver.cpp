@@ -18,7 +18,7 @@ int main() {
             unsigned long long sb;
             if (std::scanf("%d %d %d %d %llu", &M, &K, &N, &cu, &sb) != 5) return 2;
             st = dash_check_gemm_staging(M, K, N, cu, sb, &loads);
-            int plan[8] = {0};
+            int plan[10] = {0};
             dash_gemm_launch_plan(M, K, N, cu, sb, plan);
             std::printf("%d %lld %d %d\n", st, loads, plan[0], plan[2]);
         } else if (kind == 'f') {

@@ -98,24 +98,38 @@ def test_checker_catches_an_unclamped_base_row():
         assert st == 0
 
 
-def test_gemm_launch_plan_whole_rounds_half_tiles_and_k_parts():
+def test_gemm_launch_plan_whole_rounds_half_tiles_k_parts_and_tile_order():
     """How a product is cut into launches on 256 compute units: whole 256-row tiles for the whole rounds, the tiles
-    left over as half tiles when they would fill at most half of the units, K parts when all tiles do."""
+    left over as half tiles when they would fill at most half of the units, K parts when all tiles do; and which
+    tile order the whole tiles take (plain when the row tiles are a multiple of 8, else column panels dealt to the
+    XCDs in equal stretches, the grid padded to a multiple of 8)."""
     lib = _load()
     lib.dash_gemm_launch_plan.argtypes = [ctypes.c_int] * 4 + [ctypes.c_ulonglong, ctypes.POINTER(ctypes.c_int)]
     lib.dash_gemm_launch_plan.restype = None
+    names = ("tiles", "ksteps", "parts", "per_part", "full", "rest", "plain", "grid")
 
     def plan(M, K, N, cu=256, split_bytes=0):
-        out = (ctypes.c_int * 6)()
+        out = (ctypes.c_int * 10)()
         lib.dash_gemm_launch_plan(M, K, N, cu, split_bytes, out)
-        return dict(zip(("tiles", "ksteps", "parts", "per_part", "full", "rest"), out))
+        return dict(zip(names, out))
 
-    # the bench's projection: 64 x 14 = 896 tiles = 3 whole rounds + 128 tiles as 256 half tiles
-    assert plan(16384, 3584, 3584) == dict(tiles=896, ksteps=56, parts=1, per_part=56, full=768, rest=128)
+    # the bench's projection: 64 x 14 = 896 tiles = 3 whole rounds + 128 tiles as 256 half tiles; 64 row tiles: plain order
+    assert plan(16384, 3584, 3584) == dict(tiles=896, ksteps=56, parts=1, per_part=56, full=768, rest=128, plain=1,
+                                           grid=768)
     # 8192 rows: 448 tiles; the 192 left over would need more than half of the units twice over: all whole tiles
-    assert plan(8192, 3584, 3584) == dict(tiles=448, ksteps=56, parts=1, per_part=56, full=448, rest=0)
+    p = plan(8192, 3584, 3584)
+    assert (p["full"], p["rest"], p["plain"], p["grid"]) == (448, 0, 1, 448)
     # whole rounds only
     assert plan(32768, 3584, 3584)["rest"] == 0 and plan(32768, 3584, 37888)["rest"] == 0
+    # 10976 rows (kept by the single shot): 43 row tiles -> panel order; 602 tiles = 2 rounds + 90: 512 whole tiles in
+    # stretches of 64 per XCD, 90 tiles as 180 half tiles
+    p = plan(10976, 3584, 3584)
+    assert (p["full"], p["rest"], p["plain"], p["grid"]) == (512, 90, 0, 512)
+    # 11469 rows: 45 x 14 = 630 = 2 rounds + 118; 13423 rows: 53 x 14 = 742 -> 230 left over: all whole, grid padded
+    p = plan(11469, 3584, 3584)
+    assert (p["full"], p["rest"], p["plain"]) == (512, 118, 0)
+    p = plan(13423, 3584, 3584)
+    assert (p["full"], p["rest"], p["plain"], p["grid"]) == (742, 0, 0, 744)
     # 177 rows of the down projection (K = 18944): 14 tiles on 256 units -> 18 K parts of at most 17 steps
     p = plan(177, 18944, 3584, split_bytes=1 << 30)
     assert p["tiles"] == 14 and p["parts"] == 18 and p["per_part"] == 17 and 17 * 18 >= 296
@@ -124,3 +138,22 @@ def test_gemm_launch_plan_whole_rounds_half_tiles_and_k_parts():
     assert plan(177, 18944, 3584, split_bytes=177 * 3584 * 4)["parts"] == 1
     # a part never has fewer than 4 K steps: K = 256 (4 steps) cannot split
     assert plan(64, 256, 256, split_bytes=1 << 30)["parts"] == 1
+
+
+def test_checker_catches_a_wrong_work_map():
+    """A mistake planted in a copy of the header on the CPU: a stretch map that is off by one (a tile run twice,
+    another never)."""
+    src = open(os.path.join(PKG, "csrc", "staging_addr.h")).read()
+    good = "    const int idx = (b % 8) * seg + b / 8;"
+    assert good in src
+    with tempfile.TemporaryDirectory() as tmp:
+        open(os.path.join(tmp, "staging_addr.h"), "w").write(src.replace(good, "    const int idx = (b % 8) * seg + b / 8 + 1;"))
+        open(os.path.join(tmp, "staging_check.cpp"), "w").write(open(os.path.join(PKG, "csrc", "staging_check.cpp")).read())
+        out = os.path.join(tmp, "libbad.so")
+        subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", os.path.join(tmp, "staging_check.cpp"),
+                        "-o", out], check=True)
+        lib = _load(out)
+        st, _ = _gemm(lib, 10976, 3584, 3584)          # 43 row tiles: the panel order with stretches
+        assert st != 0
+        st, _ = _gemm(lib, 16384, 3584, 3584)          # 64 row tiles: plain order, the mistake does not show
+        assert st == 0
