@@ -82,10 +82,11 @@ def wo_flops(cfg, n):
 
 
 def score_compact_bytes(cfg, n, n_kept, partials_per_row, elem):
-    """Algorithmic HBM bytes of score+decision and compaction: per active row the norm partials read,
-    score (4) and mask (1) written, mask (1) and index (4) read; per kept row the hidden row read and
-    written plus the index written."""
-    per_row = 8 * partials_per_row + 4 + 1 + 1 + 4
+    """Algorithmic HBM bytes of score+decision and compaction: per active row one pair of norm partials per 256
+    output columns read (what the method needs; the kernels keep `partials_per_row` pairs, four per 256 columns),
+    score (4) and mask (1) written, index (4) read; per kept row the hidden row read and written plus the index
+    written."""
+    per_row = 8 * ((cfg.d + 255) // 256) + 4 + 1 + 4
     per_kept = 2 * cfg.d * elem + 4
     return n * per_row + n_kept * per_kept
 
@@ -536,8 +537,8 @@ def main():
                                   "unit": "TFLOP/s", "frac": both_tflops / MFMA_BF16_PEAK_TFLOPS},
         "roofline_score_compact": {"bound": "hbm", "achieved": sc_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                    "frac": sc_gbs / HBM_PEAK_GBS, "bytes": sc_bytes,
-                                   "timing": "event intervals inside the timed steps (launch gaps and event "
-                                             "records included)",
+                                   "timing": "event interval around the one launch (scores, decision, compaction) inside "
+                                             "the timed steps, launch gap and event records included",
                                    "loop": {"launch_pairs": pairs, "ms_per_pair": loop_ms,
                                             "achieved": sc_bytes / (loop_ms * 1e-3) / 1e9,
                                             "frac": sc_bytes / (loop_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,

@@ -79,7 +79,8 @@ typedef struct {
  * records HIP events on the launch stream around the four stages; read them back
  * with dash_profile_read after the stream has been synchronised by the caller. */
 typedef struct dash_profile dash_profile;
-#define DASH_N_STAGES 4 /* 0 flash attention, 1 W_o+residual+norms, 2 score+decision, 3 compaction */
+#define DASH_N_STAGES 4 /* 0 flash attention, 1 W_o+residual+norms, 2 score+decision, 3 compaction. Under the rules
+                           NONE and THRESHOLD stages 2 and 3 are one launch: its time is reported as stage 3, stage 2 as 0 */
 
 /* One-time set-up on the current device: reads the device's compute-unit count and sets the launch attributes of
  * the kernels (their LDS sizes) and looks up the device address of the static scratch of dash_decide_topk_static.

@@ -9,6 +9,7 @@ using namespace dash;
 struct dash_profile {
     hipEvent_t ev[DASH_N_STAGES + 1];
     bool recorded;
+    bool merged;  // stages 2 and 3 ran as one launch: ev[3] was not recorded
 };
 
 namespace {
@@ -34,7 +35,7 @@ dash_status check_params(const dash_layer_params* p) {
 }
 
 struct Workspace {
-    size_t o_off, partials_off, counts_off, decide_off, split_off, split_bytes, total;
+    size_t o_off, partials_off, counts_off, decide_off, published_off, split_off, split_bytes, total;
 };
 
 Workspace carve(const dash_layer_params& p, int64_t n) {
@@ -49,6 +50,8 @@ Workspace carve(const dash_layer_params& p, int64_t n) {
     off = align_up(off + n_chunks * sizeof(int32_t), 256);
     w.decide_off = off;
     off = align_up(off + decide_workspace_bytes() + n_chunks * sizeof(int32_t), 256);
+    w.published_off = off;  // words of the fused score + decision + compaction kernel
+    off = align_up(off + published_bytes((int)n), 256);
     w.split_off = off;
     w.split_bytes = wo_splitk_bytes(p, (int)n);  // split-K sums of the projection when few rows are active
     off += w.split_bytes;
@@ -184,6 +187,7 @@ dash_profile* dash_profile_create(void) {
     dash_profile* pr = new (std::nothrow) dash_profile;
     if (!pr) return nullptr;
     pr->recorded = false;
+    pr->merged = false;
     for (int i = 0; i <= DASH_N_STAGES; ++i) {
         if (hipEventCreate(&pr->ev[i]) != hipSuccess) {
             for (int k = 0; k < i; ++k) (void)hipEventDestroy(pr->ev[k]);
@@ -202,8 +206,14 @@ void dash_profile_destroy(dash_profile* pr) {
 
 dash_status dash_profile_read(dash_profile* pr, float* ms) {
     if (!pr || !ms || !pr->recorded) return DASH_ERR_INVALID_ARG;
-    for (int i = 0; i < DASH_N_STAGES; ++i)
+    for (int i = 0; i < DASH_N_STAGES; ++i) {
+        if (pr->merged && i == 2) {  // one launch for score, decision and compaction: reported as stage 3
+            ms[2] = 0.f;
+            DASH_HIP_CHECK(hipEventElapsedTime(&ms[3], pr->ev[2], pr->ev[4]));
+            break;
+        }
         DASH_HIP_CHECK(hipEventElapsedTime(&ms[i], pr->ev[i], pr->ev[i + 1]));
+    }
     return DASH_OK;
 }
 
@@ -215,7 +225,7 @@ dash_status dash_flash_fwd(const dash_layer_params* p, const void* q, const void
     if (n == 0) return DASH_OK;
     if (!q || !k || !v || !active_idx || !o) return DASH_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DASH_ERR_INVALID_ARG;
-    return launch_flash_fwd(*p, q, k, v, active_idx, n, o, (hipStream_t)hip_stream);
+    return launch_flash_fwd(*p, q, k, v, active_idx, n, o, nullptr, 0, (hipStream_t)hip_stream);
 }
 
 dash_status dash_wo_residual_rownorm(const dash_layer_params* p, const void* o, const void* w_o,
@@ -453,23 +463,35 @@ dash_status dash_attn_layer(const dash_layer_params* p, const void* x, const voi
     int32_t* counts = reinterpret_cast<int32_t*>(ws + w.counts_off);
     void* decide_ws = ws + w.decide_off;
 
+    // NONE / THRESHOLD: scores, decision and compaction run as one launch whose workgroups hand each other the
+    // chunks' kept masks through words that have to start cleared: the attention kernel clears them on its way
+    const bool one_launch = p->rule != DASH_RULE_TOPK;
+    uint32_t* published = reinterpret_cast<uint32_t*>(ws + w.published_off);
+    const int n_clear = one_launch ? (int)(published_bytes(n) / sizeof(uint32_t)) : 0;
     if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[0], s));
-    st = launch_flash_fwd(*p, q, k, v, active_idx, n, o, s);
+    st = launch_flash_fwd(*p, q, k, v, active_idx, n, o, published, n_clear, s);
     if (st != DASH_OK) return st;
     if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[1], s));
     st = launch_wo_residual_rownorm(*p, o, w_o, x, n, x_next, partials, delta_dbg, ws + w.split_off, w.split_bytes, s);
     if (st != DASH_OK) return st;
     if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[2], s));
-    st = launch_score_decide(*p, partials, norm_partials_per_row(p->d, p->dtype), n, scores, halt_mask,
-                             counts, decide_ws, s);
-    if (st != DASH_OK) return st;
-    if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[3], s));
-    st = launch_compact(halt_mask, counts, active_idx, x_next, n, p->d * (int)elem_size(p->dtype), x_compact,
-                        new_active_idx, n_active_out, s);
+    if (one_launch) {
+        st = launch_score_decide_compact(*p, partials, norm_partials_per_row(p->d, p->dtype), n, scores, halt_mask,
+                                         published, active_idx, x_next, p->d * (int)elem_size(p->dtype), x_compact,
+                                         new_active_idx, n_active_out, s);
+    } else {
+        st = launch_score_decide(*p, partials, norm_partials_per_row(p->d, p->dtype), n, scores, halt_mask,
+                                 counts, decide_ws, s);
+        if (st != DASH_OK) return st;
+        if (profile) DASH_HIP_CHECK(hipEventRecord(profile->ev[3], s));
+        st = launch_compact(halt_mask, counts, active_idx, x_next, n, p->d * (int)elem_size(p->dtype), x_compact,
+                            new_active_idx, n_active_out, s);
+    }
     if (st != DASH_OK) return st;
     if (profile) {
         DASH_HIP_CHECK(hipEventRecord(profile->ev[4], s));
         profile->recorded = true;
+        profile->merged = one_launch;
     }
     return DASH_OK;
 }

@@ -50,8 +50,11 @@ dash_status init_flash_kernels();
 dash_status init_gemm_kernels();
 
 // flash_fwd.hip
+// clear_words / n_clear: optional device words the launch sets to zero (its first workgroup does it), for the
+// kernels that follow in the same layer call and need cleared scratch without a launch of their own
 dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const void* k, const void* v,
-                             const int32_t* active_idx, int n, void* o, hipStream_t s);
+                             const int32_t* active_idx, int n, void* o, uint32_t* clear_words, int n_clear,
+                             hipStream_t s);
 // wo_gemm.hip
 int norm_partials_per_row(int d, int dtype);
 // split_ws / split_bytes: optional device scratch that lets products with few output tiles split along K
@@ -75,6 +78,11 @@ dash_status launch_score_decide(const dash_layer_params& p, const float* partial
 dash_status launch_score_rows(const float* delta, const void* x, int n, int d, int dtype, int kind,
                               float* scores, hipStream_t s);
 // compact.hip
+size_t published_bytes(int n);  // words the fused score + decision + compaction kernel publishes its chunks through
+dash_status launch_score_decide_compact(const dash_layer_params& p, const float* partials, int n_partials, int n,
+                                        float* scores, uint8_t* halt, void* published, const int32_t* active_idx,
+                                        const void* x_next, int row_bytes, void* x_compact, int32_t* new_active_idx,
+                                        int32_t* n_active_out, hipStream_t s);
 dash_status launch_chunk_counts(const uint8_t* halt, int n, int32_t* chunk_counts, hipStream_t s);
 dash_status launch_compact(const uint8_t* halt, const int32_t* chunk_counts, const int32_t* active_idx,
                            const void* x_next, int n, int row_bytes, void* x_compact,

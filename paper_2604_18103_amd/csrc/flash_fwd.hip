@@ -22,8 +22,11 @@ template <typename T, int DH>
 __global__ __launch_bounds__(64) void flash_fwd_simple(const T* __restrict__ q, const T* __restrict__ k,
                                                        const T* __restrict__ v,
                                                        const int32_t* __restrict__ pos, T* __restrict__ o,
-                                                       int n, int Hq, int Hkv, float scale, int causal) {
+                                                       int n, int Hq, int Hkv, float scale, int causal,
+                                                       uint32_t* __restrict__ clear_words, int n_clear) {
     constexpr int DPL = DH / kWave;  // head dims per lane
+    if (blockIdx.x == 0 && blockIdx.y == 0)  // scratch of the kernels that follow in the layer call
+        for (int c = threadIdx.x; c < n_clear; c += kWave) clear_words[c] = 0u;
     __shared__ float qs[DH];
     const int i = blockIdx.x, h = blockIdx.y, lane = threadIdx.x;
     const int g = h / (Hq / Hkv);
@@ -188,7 +191,8 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
                                                                 const int32_t* __restrict__ pos,
                                                                 __bf16* __restrict__ o, int n, int Hq,
                                                                 int Hkv, float scale_log2, int causal,
-                                                                int n_qtiles, FaMap mp) {
+                                                                int n_qtiles, FaMap mp,
+                                                                uint32_t* __restrict__ clear_words, int n_clear) {
     using SM = FaSmem<DH>;
     constexpr int KC = DH / 16;  // contraction chunks of Q K^T
     constexpr int DB = DH / 32;  // 32-wide output blocks of O^T
@@ -197,6 +201,8 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     __bf16* Vst = Kst + 2 * SM::STAGE_ELEMS;
     __shared__ __attribute__((aligned(16))) int pos_blk[kFaBM];  // original positions of this workgroup's rows
 
+    if (blockIdx.x == 0)  // scratch of the kernels that follow in the layer call: cleared here, no launch of its own
+        for (int c = threadIdx.x; c < n_clear; c += kFaThreads) clear_words[c] = 0u;
     int qt, head;
     if (!fa_map_block(mp, (int)blockIdx.x, n_qtiles, Hq, Hkv, qt, head)) return;  // whole workgroup exits
     const int g = head / (Hq / Hkv);
@@ -529,14 +535,15 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
 
 template <typename T>
 static dash_status launch_simple(const dash_layer_params& p, const T* q, const T* k, const T* v,
-                                 const int32_t* pos, int n, T* o, float scale, hipStream_t s) {
+                                 const int32_t* pos, int n, T* o, float scale, uint32_t* clear_words, int n_clear,
+                                 hipStream_t s) {
     dim3 grid(n, p.n_q_heads);
     if (p.head_dim == 64)
         hipLaunchKernelGGL((flash_fwd_simple<T, 64>), grid, dim3(64), 0, s, q, k, v, pos, o, n, p.n_q_heads,
-                           p.n_kv_heads, scale, p.causal);
+                           p.n_kv_heads, scale, p.causal, clear_words, n_clear);
     else
         hipLaunchKernelGGL((flash_fwd_simple<T, 128>), grid, dim3(64), 0, s, q, k, v, pos, o, n, p.n_q_heads,
-                           p.n_kv_heads, scale, p.causal);
+                           p.n_kv_heads, scale, p.causal, clear_words, n_clear);
     return launch_status();
 }
 
@@ -553,12 +560,13 @@ dash_status init_flash_kernels() {
 }
 
 dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const void* k, const void* v,
-                             const int32_t* active_idx, int n, void* o, hipStream_t s) {
+                             const int32_t* active_idx, int n, void* o, uint32_t* clear_words, int n_clear,
+                             hipStream_t s) {
     if (n == 0) return DASH_OK;
     const float scale = p.softmax_scale > 0.f ? p.softmax_scale : 1.0f / sqrtf((float)p.head_dim);
     if (p.dtype == DASH_F32)
         return launch_simple<float>(p, (const float*)q, (const float*)k, (const float*)v, active_idx, n,
-                                    (float*)o, scale, s);
+                                    (float*)o, scale, clear_words, n_clear, s);
     // the MFMA kernel addresses K and V with 32-bit byte offsets
     if ((size_t)n * p.n_kv_heads * p.head_dim * 2 >= (size_t)1 << 31) return DASH_ERR_UNSUPPORTED;
     const int n_qtiles = (n + kFaBM - 1) / kFaBM;
@@ -580,11 +588,11 @@ dash_status launch_flash_fwd(const dash_layer_params& p, const void* q, const vo
     if (p.head_dim == 64) {
         hipLaunchKernelGGL((flash_fwd_mfma<64>), grid, dim3(kFaThreads), FaSmem<64>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
-                           p.causal, n_qtiles, mp);
+                           p.causal, n_qtiles, mp, clear_words, n_clear);
     } else {
         hipLaunchKernelGGL((flash_fwd_mfma<128>), grid, dim3(kFaThreads), FaSmem<128>::BYTES, s, (const __bf16*)q,
                            (const __bf16*)k, (const __bf16*)v, active_idx, (__bf16*)o, n, Hq, Hkv, scale_log2,
-                           p.causal, n_qtiles, mp);
+                           p.causal, n_qtiles, mp, clear_words, n_clear);
     }
     return launch_status();
 }

@@ -276,3 +276,66 @@ def test_flash_softmax_reference_moves_with_the_scores(dh, slope):
         err = P.row_rel_err(got, want)
         print("drift", dh, slope, causal, float(err.max()))
         assert err.max() <= P.X_TOL["bf16"], (causal, float(err.max()))
+
+
+@pytest.mark.parametrize("n,d,prot", [(1, 256, (0, 0)), (63, 256, (3, 2)), (65, 256, (0, 0)), (1333, 512, (64, 32)),
+                                      (20001, 256, (0, 0)), (131072, 128, (5, 7))],
+                         ids=lambda v: str(v).replace(" ", ""))
+def test_layer_call_in_one_launch_equals_the_staged_calls(n, d, prot):
+    """Under the rules NONE and THRESHOLD the layer call finishes scores, decision and compaction in one launch whose
+    workgroups hand each other the chunks' kept masks and counts; the stage-level calls (score + decision, then
+    compaction, two launches) compute the same from the same norm partials. Every output must be bit-identical,
+    from one chunk to 2048 chunks (n = 131072), twice in a row on the same buffers (the published words of the
+    first call are cleared by the second)."""
+    rng = np.random.default_rng(n)
+    hq, dh = d // 64, 64
+    p = B.make_params(d, hq, hq, dh, rule=B.RULE_THRESHOLD, keep_first_n=prot[0], keep_last_n=prot[1])
+    N = 3 * n + 5
+    idx = torch.from_numpy(np.sort(rng.choice(N, size=n, replace=False)).astype(np.int32)).cuda()
+    bf = torch.bfloat16
+    g = torch.Generator(device="cuda").manual_seed(n)
+    rnd = lambda *shape: torch.randn(shape, generator=g, device="cuda", dtype=torch.float32)
+    x = (rnd(n, d) * torch.exp(1.5 * rnd(n, 1))).to(bf)
+    w_o = (rnd(hq * dh, d) / d ** 0.5).to(bf)
+    o = rnd(n, hq * dh).to(bf)                      # any attention output: only to draw a threshold from real scores
+    P_ = B.norm_partials_per_row(p)
+    # staged: projection, score + decision, compaction
+    x_next = torch.empty((n, d), dtype=bf, device="cuda")
+    partials = torch.empty((P_, n, 2), dtype=torch.float32, device="cuda")
+    B.dash_wo_residual_rownorm(p, o, w_o, x, n, x_next, partials, None, None)
+    scores = torch.empty((n,), dtype=torch.float32, device="cuda")
+    halt = torch.empty((n,), dtype=torch.uint8, device="cuda")
+    counts = torch.empty(((n + 63) // 64,), dtype=torch.int32, device="cuda")
+    p.rule = B.RULE_NONE
+    B.dash_score_decide(p, partials, n, scores, halt, counts)
+    torch.cuda.synchronize()
+    tau, h = I.percentile_tau(scores.cpu().numpy(), 0.37)
+    for rule, tau_ in ((B.RULE_THRESHOLD, tau), (B.RULE_NONE, 0.0), (B.RULE_THRESHOLD, float("inf")),
+                       (B.RULE_THRESHOLD, tau)):
+        p.rule, p.tau = rule, tau_
+        x_c = torch.full((n, d), float("nan"), dtype=bf, device="cuda")
+        new_idx = torch.full((n,), -1, dtype=torch.int32, device="cuda")
+        n_out = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+        buf = B.alloc_layer_buffers(p, n, with_delta=True)   # the debug output keeps both paths off split-K
+        q = rnd(n, hq, dh).to(bf)
+        kk = rnd(n, hq, dh).to(bf)
+        v = rnd(n, hq, dh).to(bf)
+        B.dash_attn_layer(p, x, q, kk, v, w_o, idx, n, buf)
+        B.dash_attn_layer(p, x, q, kk, v, w_o, idx, n, buf)          # again on the same workspace
+        o2 = torch.empty((n, hq * dh), dtype=bf, device="cuda")
+        B.dash_flash_fwd(p, q, kk, v, idx, n, o2)
+        B.dash_wo_residual_rownorm(p, o2, w_o, x, n, x_next, partials, buf.delta_dbg, None)
+        B.dash_score_decide(p, partials, n, scores, halt, counts)
+        x_c.fill_(float("nan"))
+        B.dash_compact(p, halt, counts, idx, x_next, n, x_c, new_idx, n_out)
+        torch.cuda.synchronize()
+        k = int(n_out.item())
+        assert int(buf.n_active_out.item()) == k
+        assert torch.equal(buf.x_next[:n], x_next)
+        assert torch.equal(buf.scores[:n], scores) and torch.equal(buf.halt_mask[:n], halt)
+        assert torch.equal(buf.new_active_idx[:k], new_idx[:k])
+        assert torch.equal(buf.x_compact[:k], x_c[:k])
+        if rule == B.RULE_NONE:
+            assert k == n
+        if tau_ == float("inf"):
+            assert k == min(n, prot[0] + prot[1])
