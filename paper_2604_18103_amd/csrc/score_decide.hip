@@ -69,19 +69,63 @@ constexpr int kSelectThreads = 1024;
 constexpr int kSelectBins = 2048;   // histogram bins of one radix pass (11-bit digits)
 constexpr int kSelectBatch = 16;    // scores a thread has in flight per load batch
 
+struct SelectShared {
+    int hist[kSelectBins];
+    int wave_tot[kSelectThreads / kWave];
+    uint32_t prefix;
+    int remaining, ties;
+};
+
+// After a pass has filled sh.hist (and a barrier): the bin that holds the remaining-th largest key, i.e. the largest
+// b with (keys in bins >= b) >= remaining; updates prefix and remaining (uniform) and leaves the bin's count in
+// sh.ties. Thread t owns bins 2t and 2t + 1; suffix sums over the threads of a wave by shuffles, over the waves
+// through LDS. Called by all kSelectThreads threads; ends with a barrier after which sh.hist may be cleared.
+__device__ __forceinline__ void select_bin(SelectShared& sh, int shift, uint32_t& prefix, int& remaining) {
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+    int suf = h0 + h1;  // becomes the count of keys in bins >= 2 tid
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int t = __shfl_down(suf, o);
+        if (lane + o < kWave) suf += t;
+    }
+    if (lane == 0) sh.wave_tot[wave] = suf;
+    __syncthreads();
+    for (int w = wave + 1; w < kSelectThreads / kWave; ++w) suf += sh.wave_tot[w];
+    // exactly one bin satisfies excl < remaining <= incl (the keys under the prefix number at least `remaining`)
+    const int incl1 = suf - h0, excl1 = incl1 - h1;  // bin 2 tid + 1
+    const int incl0 = suf, excl0 = incl1;            // bin 2 tid
+    if (excl1 < remaining && remaining <= incl1) {
+        sh.prefix = prefix | ((uint32_t)(2 * tid + 1) << shift);
+        sh.remaining = remaining - excl1;
+        sh.ties = h1;
+    } else if (excl0 < remaining && remaining <= incl0) {
+        sh.prefix = prefix | ((uint32_t)(2 * tid) << shift);
+        sh.remaining = remaining - excl0;
+        sh.ties = h0;
+    }
+    __syncthreads();
+    prefix = sh.prefix;
+    remaining = sh.remaining;
+}
+
+__device__ __forceinline__ int pass_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ uint32_t pass_digit_mask(int pass) { return pass == 2 ? 0x3FFu : 0x7FFu; }
+__device__ __forceinline__ uint32_t pass_high_mask(int pass) {
+    return pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
+}
+
 // TopK selection (Eq. 3): one workgroup finds the key of the k_cand-th largest score among the unprotected rows by
 // three radix passes over the order-preserving keys (digits of 11, 11 and 10 bits, integer histograms in LDS: the
 // order of the adds does not matter, so the result is exact and reproducible). A pass streams the scores with 16
-// independent loads per thread in flight, so its time is a few memory latencies, not one per 1024 rows. When more
+// independent loads per thread in flight, so its time is a few memory latencies plus the adds, not a latency per
+// 1024 rows. When more
 // rows tie with the K-th key than may be kept, it also counts those ties per 64-row chunk, so the flag kernel can
 // keep the earliest ones; with distinct scores (the usual case) that pass over the scores is skipped.
 __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, int keep_low,
     TopkState* __restrict__ st, int32_t* __restrict__ tie_counts) {
-    __shared__ int hist[kSelectBins];
-    __shared__ int wave_tot[kSelectThreads / kWave];
-    __shared__ uint32_t sh_prefix;
-    __shared__ int sh_remaining, sh_ties;
+    __shared__ SelectShared sh;
     const int tid = threadIdx.x;
     const int lane = tid % kWave, wave = tid / kWave;
     const int lo = min(n_first, n), hi = max(lo, n - n_last);  // candidates are rows [lo, hi)
@@ -102,10 +146,9 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     int remaining = k_cand;    // rank of the wanted key among the keys that share the prefix, uniform
 #pragma unroll 1
     for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-        const uint32_t digit_mask = pass == 2 ? 0x3FFu : 0x7FFu;
-        const uint32_t hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (pass == 1 ? 21 : 10));
-        for (int b = tid; b < kSelectBins; b += kSelectThreads) hist[b] = 0;
+        const int shift = pass_shift(pass);
+        const uint32_t digit_mask = pass_digit_mask(pass), hi_mask = pass_high_mask(pass);
+        for (int b = tid; b < kSelectBins; b += kSelectThreads) sh.hist[b] = 0;
         __syncthreads();
         for (int r0 = lo; r0 < hi; r0 += kSelectThreads * kSelectBatch) {
             float v[kSelectBatch];
@@ -118,65 +161,17 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
             for (int u = 0; u < kSelectBatch; ++u) {
                 const int r = r0 + u * kSelectThreads + tid;
                 const uint32_t key = rank_key(v[u], keep_low);
-                bool mine = r < hi && (key & hi_mask) == prefix;
-                const uint32_t bin = (key >> shift) & digit_mask;
-                // Scores of one layer share a few exponents, so most lanes of a wave hit the same one or two bins
-                // in the first pass: those are counted with one ballot and one add per bin, the rest add on their own.
-                if (pass == 0) {
-#pragma unroll
-                    for (int it = 0; it < 2; ++it) {
-                        const unsigned long long todo = __ballot(mine);
-                        if (todo == 0ull) break;
-                        const int leader = __ffsll((long long)todo) - 1;
-                        const uint32_t lb = (uint32_t)__shfl((int)bin, leader);
-                        const unsigned long long same = __ballot(mine && bin == lb);
-                        if (lane == leader) atomicAdd(&hist[lb], (int)__popcll(same));
-                        if (bin == lb) mine = false;
-                    }
-                }
-                if (mine) atomicAdd(&hist[bin], 1);
+                // plain LDS adds: with 11-bit digits the keys of a wave spread over many bins (folding the lanes that
+                // share a bin into one add by ballots measured a third slower on the workloads' scores; it only pays
+                // for heavily tied scores, which stay correct and 3-6 times slower)
+                if (r < hi && (key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1);
             }
         }
         __syncthreads();
-        // The bin that holds the remaining-th largest key: the largest b with (keys in bins >= b) >= remaining.
-        // Thread t owns bins 2t and 2t + 1; suffix sums over the threads of a wave by shuffles, over the waves
-        // through LDS.
-        const int h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
-        int suf = h0 + h1;  // becomes the count of keys in bins >= 2 tid
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const int t = __shfl_down(suf, o);
-            if (lane + o < kWave) suf += t;
-        }
-        if (lane == 0) wave_tot[wave] = suf;
-        __syncthreads();
-        for (int w = wave + 1; w < kSelectThreads / kWave; ++w) suf += wave_tot[w];
-        // exactly one bin satisfies excl < remaining <= incl (the keys under the prefix number at least `remaining`)
-        const int incl1 = suf - h0, excl1 = incl1 - h1;  // bin 2 tid + 1
-        const int incl0 = suf, excl0 = incl1;            // bin 2 tid
-        int found = -1, found_excl = 0, found_cnt = 0;
-        if (excl1 < remaining && remaining <= incl1) {
-            found = 2 * tid + 1;
-            found_excl = excl1;
-            found_cnt = h1;
-        } else if (excl0 < remaining && remaining <= incl0) {
-            found = 2 * tid;
-            found_excl = excl0;
-            found_cnt = h0;
-        }
-        if (found >= 0) {
-            sh_prefix = prefix | ((uint32_t)found << shift);
-            sh_remaining = remaining - found_excl;
-            sh_ties = found_cnt;  // after the last pass: rows whose key equals the threshold key
-        }
-        __syncthreads();
-        prefix = sh_prefix;
-        remaining = sh_remaining;
-        // the next pass clears hist only after every thread has passed this barrier and read its bins
+        select_bin(sh, shift, prefix, remaining);
     }
     const uint32_t T = prefix;
-    const int ties = sh_ties;
-    const bool rank_ties = ties > remaining;  // more rows tie with the K-th key than may be kept
+    const bool rank_ties = sh.ties > remaining;  // more rows tie with the K-th key than may be kept
     if (tid == 0) {
         st->threshold_key = T;
         st->tie_quota = remaining;  // >= 1: ties (key == T) still to be kept
