@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a
 # copy kernel of known size (see profiles/hbm_traffic_and_pipe_counters_qwen_32k_half.md); offline
 # measurements, so only the workload they were taken on has one.
-FLASH_TRAFFIC_BYTES = {"qwen_32k_half": 388e6 + 117e6}
+FLASH_TRAFFIC_BYTES = {"qwen_32k_half": 398e6 + 117e6}
 
 
 def measure_mfma_peak(seconds_per_case=0.25):
