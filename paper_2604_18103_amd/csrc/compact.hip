@@ -187,7 +187,7 @@ __global__ __launch_bounds__(kCompactThreads) void score_decide_compact_kernel(
         if (chunk == (int)gridDim.x - 1 && lane == 0) *n_out = failed ? -1 : base + cnt;
     }
     if (failed) return;  // uniform: every thread read the same LDS words
-    const int v0 = blockIdx.y * vecs_per_split;
+    const int v0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * vecs_per_split;
     const int v1 = min(row_vecs, v0 + vecs_per_split);
     constexpr int R = 4;
     for (int r0 = wave * R; r0 < cnt; r0 += kCompactWaves * R) {

@@ -8,7 +8,7 @@
 // Also here: the front end used by a chain of layers (RMSNorm + q/k/v projections), which shares the
 // MFMA main loop with a plain store epilogue.
 //
-// norm_partials layout: [P][n][2] fp32, P = column tiles (x wave columns) of the kernel in use.
+// norm_partials layout: [P][n][2] fp32, P = column tiles of the kernel in use (256 columns; 64 in the fp32 kernel).
 #include "common.h"
 #include "staging_addr.h"
 
@@ -114,7 +114,8 @@ constexpr int kGAElems = kGM * kGK, kGBElems = kGK * kGN;
 constexpr int kGStageElems = kGAElems + kGBElems;
 constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (131072 B)
 constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row (conflict-free 16-byte reads of two rows by 16 lanes)
-static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float), "epilogue staging must fit");
+static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float) + 4 * kGM * 2 * sizeof(float),
+              "epilogue staging and the row-sum exchange must fit");
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -340,6 +341,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     // handles 8 consecutive columns of one row - 16-byte x loads, 16-byte x_next stores, in-row sums over
     // 8 lanes. The x vectors of the next block are fetched before the current one is processed.
     float* stage = reinterpret_cast<float*>(gemm_smem_raw) + wave * 32 * kEpiStr;
+    float2* nrm = reinterpret_cast<float2*>(gemm_smem_raw + kGWaves * 32 * kEpiStr * sizeof(float));  // [4 wave columns][BM rows]
     const int e_row = lane / 8, e_c8 = lane % 8;
     const int gn_e = n0 + wn * 64 + 8 * e_c8;
     const bool col_ok = gn_e < N;
@@ -348,7 +350,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
 #pragma unroll
         for (int step = 0; step < 4; ++step) {
             const int gm = min(m0 + wm * WM + 32 * a + 8 * step + e_row, M - 1);
-            dst[step] = *reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + min(gn_e, N - 8));
+            dst[step] = __builtin_nontemporal_load(reinterpret_cast<const bf16x8*>(x + (size_t)gm * N + min(gn_e, N - 8)));
         }
     };
     if (EPI == EPI_RESIDUAL_NORM) fetch_x(0, xv[0]);
@@ -418,10 +420,8 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                     sd += __shfl_xor(sd, off);
                     sx += __shfl_xor(sx, off);
                 }
-                if (e_c8 == 0 && gm < M) {
-                    const int p = tile_n * 4 + wn;
-                    *reinterpret_cast<float2*>(partials + ((size_t)p * M + gm) * 2) = make_float2(sd, sx);
-                }
+                // the four wave columns of the tile meet in LDS; one pair per row and tile is written after the loop
+                if (e_c8 == 0) nrm[wn * BM + wm * WM + 32 * a + lr] = make_float2(sd, sx);
             } else if (EPI == EPI_SPLITK) {
                 if (ok) {
                     float* dst = f32_out + ((size_t)blockIdx.y * M + gm) * N + gn_e;
@@ -438,11 +438,26 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         }
         __syncthreads();
     }
+    if (EPI == EPI_RESIDUAL_NORM) {
+        // row sums of the tile's 256 columns: the wave columns in the fixed order 0..3
+        for (int r = tid; r < BM; r += kGThreads) {
+            const int gm = m0 + r;
+            if (gm < M) {
+                float2 t = nrm[r];
+#pragma unroll
+                for (int w = 1; w < 4; ++w) {
+                    t.x += nrm[w * BM + r].x;
+                    t.y += nrm[w * BM + r].y;
+                }
+                *reinterpret_cast<float2*>(partials + ((size_t)tile_n * M + gm) * 2) = t;
+            }
+        }
+    }
 }
 
 // Second pass of a split-K product: adds the S split sums of sums[S][M][N] in the order s = 0..S-1 and applies
 // the epilogue EPI (same results layout as the one-pass kernel). A wave works on one row; a lane owns 8
-// consecutive columns, so the 8 lanes of a 64-column group hold that group's row sums for the norm partials.
+// consecutive columns, so the 32 lanes of a 256-column tile hold that tile's row sums for the norm partials.
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ sums, int S, int M, int N,
                                                             const __bf16* __restrict__ x, __bf16* __restrict__ out,
@@ -517,15 +532,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         }
         *reinterpret_cast<bf16x8*>(out + (size_t)row * N + col) = ov;
     }
+    // one partial pair per 256-column tile, as the one-pass kernel writes them: the 32 lanes of a tile in fixed order
 #pragma unroll
-    for (int off = 4; off > 0; off >>= 1) {
+    for (int off = 1; off < 32; off <<= 1) {
         sd += __shfl_xor(sd, off);
         sx += __shfl_xor(sx, off);
     }
-    // one partial pair per 64-column group, as the one-pass kernel writes them; groups beyond N (the rest of a
-    // 256-column tile) hold zeros
-    if (lane % 8 == 0 && grp < 4 * ((N + kGN - 1) / kGN))
-        *reinterpret_cast<float2*>(partials + ((size_t)grp * M + row) * 2) = make_float2(sd, sx);
+    const int tile = seg * 2 + lane / 32;
+    if (lane % 32 == 0 && tile < (N + kGN - 1) / kGN)
+        *reinterpret_cast<float2*>(partials + ((size_t)tile * M + row) * 2) = make_float2(sd, sx);
 }
 
 // h = x / sqrt(mean(x^2) + 1e-6), unit gain; one wave per row. Rows of up to 512 * CH elements are held in
@@ -594,7 +609,7 @@ static void launch_rmsnorm(const __bf16* x, int n, int d, __bf16* h, hipStream_t
 
 int norm_partials_per_row(int d, int dtype) {
     if (dtype == DASH_F32) return (d + kSimpleTile - 1) / kSimpleTile;
-    return 4 * ((d + kGN - 1) / kGN);
+    return (d + kGN - 1) / kGN;
 }
 
 // Number of compute units of the current device (queried once; the library serves one GPU).
