@@ -83,7 +83,7 @@ def wo_flops(cfg, n):
 
 def score_compact_bytes(cfg, n, n_kept, partials_per_row, elem):
     """Algorithmic HBM bytes of score+decision and compaction: per active row one pair of norm partials per 256
-    output columns read (what the method needs; the kernels keep `partials_per_row` pairs, four per 256 columns),
+    output columns read (`partials_per_row` of them: what the GEMM epilogue writes per row),
     score (4) and mask (1) written, index (4) read; per kept row the hidden row read and written plus the index
     written."""
     per_row = 8 * ((cfg.d + 255) // 256) + 4 + 1 + 4

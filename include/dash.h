@@ -186,6 +186,8 @@ dash_status dash_decide_topk(const dash_layer_params *params, const float *score
  * the selection state and tie counts live in a device array that is part of the library image
  * (256 + 4 * DASH_TOPK_STATIC_MAX_ROWS / 64 bytes = 65 792 bytes on every GPU the library runs on, held until the
  * process ends). Allocates nothing and frees nothing. n > DASH_TOPK_STATIC_MAX_ROWS returns DASH_ERR_UNSUPPORTED.
+ * It runs the selection and flag kernels at every size (dash_decide_topk takes a one-launch kernel that needs no
+ * scratch up to 16384 rows, 1-2 us faster there).
  * The first call on a device (or dash_init() with that device current) looks up the array's device address; do
  * that outside a graph capture. All calls on one GPU share that GPU's array, which keeps the last call's contents
  * (the kernels overwrite what they read, nothing needs clearing): calls that overlap on one GPU (different

@@ -272,7 +272,7 @@ dash_status dash_decide_topk(const dash_layer_params* p, const float* scores, in
     if (p->k_keep < 0 && !(p->rho >= 0.0 && p->rho < 1.0)) return DASH_ERR_INVALID_ARG;
     const size_t need = decide_workspace_bytes() + (size_t)((n + kChunkRows - 1) / kChunkRows) * 4;
     if (!workspace || workspace_bytes < need || !aligned16(workspace)) return DASH_ERR_WORKSPACE;
-    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace,
+    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, workspace, true,
                               (hipStream_t)hip_stream);
 }
 
@@ -288,8 +288,10 @@ dash_status dash_decide_topk_static(const dash_layer_params* p, const float* sco
     void* scratch = nullptr;
     st = topk_static_scratch_ptr(&scratch);
     if (st != DASH_OK) return st;
-    // the kernels write the selection state and every tie count they later read, so nothing has to be cleared
-    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, scratch, (hipStream_t)hip_stream);
+    // the kernels write the selection state and every tie count they later read, so nothing has to be cleared; this
+    // entry point always takes the selection + flag kernels, which keep their state in the scratch
+    return launch_decide_topk(*p, scores, n, keep_low, halt_mask, chunk_keep_counts, scratch, false,
+                              (hipStream_t)hip_stream);
 }
 
 dash_status dash_score_diff_rows(const void* x_new, const void* x_old, int32_t n, int32_t d, int32_t dtype,

@@ -93,7 +93,7 @@ dash_status launch_ffn_swiglu(const dash_layer_params& p, const void* x, const v
 dash_status launch_scatter_rows(const void* rows, const int32_t* idx, const uint8_t* sel, int sel_value, int n,
                                 int d, int dtype, int N, void* full, hipStream_t s);
 dash_status launch_decide_topk(const dash_layer_params& p, const float* scores, int n, int keep_low, uint8_t* halt,
-                               int32_t* chunk_counts, void* ws, hipStream_t s);
+                               int32_t* chunk_counts, void* ws, bool one_launch_allowed, hipStream_t s);
 dash_status launch_score_diff_rows(const void* x_new, const void* x_old, int n, int d, int dtype, int kind,
                                    float* scores, hipStream_t s);
 dash_status launch_rope_qk(const dash_layer_params& p, void* q, void* k, const int32_t* active_idx, int n,

@@ -68,21 +68,41 @@ struct TopkState {
 constexpr int kSelectThreads = 1024;
 constexpr int kSelectBins = 2048;   // histogram bins of one radix pass (11-bit digits)
 constexpr int kSelectBatch = 16;    // scores a thread has in flight per load batch
+// Copies of the histogram, one per lane % kHistCopies: adds of one wave instruction to the same LDS word are done one
+// after the other, and scores that crowd into a few bins of the first pass (sign, exponent and two mantissa bits:
+// the relative scores of one layer may span only an octave or two) make that pass several times longer. Two copies
+// cost the widely spread case 5 % and take a third off the crowded ones; four cost more than they return.
+constexpr int kHistCopies = 2;
 
 struct SelectShared {
-    int hist[kSelectBins];
+    int hist[kSelectBins][kHistCopies];  // the copies of a bin side by side: in different LDS banks
     int wave_tot[kSelectThreads / kWave];
     uint32_t prefix;
     int remaining, ties;
 };
+
+__device__ __forceinline__ void clear_hist(SelectShared& sh) {
+    int* h = &sh.hist[0][0];
+    for (int b = threadIdx.x; b < kHistCopies * kSelectBins; b += kSelectThreads) h[b] = 0;
+}
+
+__device__ __forceinline__ void hist_add(SelectShared& sh, uint32_t digit) {
+    atomicAdd(&sh.hist[digit][threadIdx.x % kHistCopies], 1);
+}
 
 // After a pass has filled sh.hist (and a barrier): the bin that holds the remaining-th largest key, i.e. the largest
 // b with (keys in bins >= b) >= remaining; updates prefix and remaining (uniform) and leaves the bin's count in
 // sh.ties. Thread t owns bins 2t and 2t + 1; suffix sums over the threads of a wave by shuffles, over the waves
 // through LDS. Called by all kSelectThreads threads; ends with a barrier after which sh.hist may be cleared.
 __device__ __forceinline__ void select_bin(SelectShared& sh, int shift, uint32_t& prefix, int& remaining) {
+    constexpr int kWaves = kSelectThreads / kWave;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const int h0 = sh.hist[2 * tid], h1 = sh.hist[2 * tid + 1];
+    int h0 = 0, h1 = 0;
+#pragma unroll
+    for (int c = 0; c < kHistCopies; ++c) {
+        h0 += sh.hist[2 * tid][c];
+        h1 += sh.hist[2 * tid + 1][c];
+    }
     int suf = h0 + h1;  // becomes the count of keys in bins >= 2 tid
 #pragma unroll
     for (int o = 1; o < kWave; o <<= 1) {
@@ -91,7 +111,11 @@ __device__ __forceinline__ void select_bin(SelectShared& sh, int shift, uint32_t
     }
     if (lane == 0) sh.wave_tot[wave] = suf;
     __syncthreads();
-    for (int w = wave + 1; w < kSelectThreads / kWave; ++w) suf += sh.wave_tot[w];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) {  // every total is read (independent LDS reads), the later waves' are added
+        const int t = sh.wave_tot[w];
+        if (w > wave) suf += t;
+    }
     // exactly one bin satisfies excl < remaining <= incl (the keys under the prefix number at least `remaining`)
     const int incl1 = suf - h0, excl1 = incl1 - h1;  // bin 2 tid + 1
     const int incl0 = suf, excl0 = incl1;            // bin 2 tid
@@ -148,7 +172,7 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
     for (int pass = 0; pass < 3; ++pass) {
         const int shift = pass_shift(pass);
         const uint32_t digit_mask = pass_digit_mask(pass), hi_mask = pass_high_mask(pass);
-        for (int b = tid; b < kSelectBins; b += kSelectThreads) sh.hist[b] = 0;
+        clear_hist(sh);
         __syncthreads();
         for (int r0 = lo; r0 < hi; r0 += kSelectThreads * kSelectBatch) {
             float v[kSelectBatch];
@@ -164,7 +188,7 @@ __global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(
                 // plain LDS adds: with 11-bit digits the keys of a wave spread over many bins (folding the lanes that
                 // share a bin into one add by ballots measured a third slower on the workloads' scores; it only pays
                 // for heavily tied scores, which stay correct and 3-6 times slower)
-                if (r < hi && (key & hi_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & digit_mask], 1);
+                if (r < hi && (key & hi_mask) == prefix) hist_add(sh, (key >> shift) & digit_mask);
             }
         }
         __syncthreads();
@@ -242,6 +266,106 @@ __global__ __launch_bounds__(256) void topk_flag_kernel(const float* __restrict_
     if (lane == 0) chunk_counts[chunk] = __popcll(m);
 }
 
+// TopK decision (Eq. 3) of up to 1024 * B rows in ONE launch of one workgroup: selection and flags together.
+// Thread t holds the keys of rows u * 1024 + t (u < B) in registers, so the scores are read once: the three radix
+// passes, the flags and the kept counts per 64-row chunk (chunk u * 16 + w is what wave w holds at step u) all work
+// from those registers. Same total order, same tie rule (earliest rows first) and same outputs as the
+// topk_select_kernel + topk_flag_kernel pair, which serves longer inputs. One compute unit does all of it, so the
+// time is that unit's instruction throughput (about 20 vector instructions per row over the three passes and the
+// flags), not memory: 16-byte loads with four flags per store, and the keys in LDS under short rolled loops,
+// measured slower than this plain form.
+template <int B>
+__global__ __launch_bounds__(kSelectThreads) void topk_decide_small_kernel(
+    const float* __restrict__ scores, int n, int n_first, int n_last, int k_keep, int keep_low,
+    uint8_t* __restrict__ halt, int32_t* __restrict__ chunk_counts) {
+    constexpr int kWaves = kSelectThreads / kWave;
+    constexpr int kChunks = B * kWaves;
+    __shared__ SelectShared sh;
+    __shared__ int tie_base[kChunks];  // ties per chunk, then ties in all earlier chunks
+    const int tid = threadIdx.x;
+    const int lane = tid % kWave, wave = tid / kWave;
+    const int lo = min(n_first, n), hi = max(lo, n - n_last);  // candidates are rows [lo, hi)
+    const int n_cand = hi - lo;
+    const int k_cand = max(0, min(k_keep - (n - n_cand), n_cand));
+    uint32_t key[B];
+    uint32_t cand = 0u;  // bit u: row u * 1024 + tid is a candidate
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+        const int r = u * kSelectThreads + tid;
+        key[u] = rank_key(r < n ? scores[r] : 0.f, keep_low);
+        if (r >= lo && r < hi) cand |= 1u << u;
+    }
+    // nothing unprotected survives: no key exceeds the threshold and no tie is kept
+    uint32_t T = 0xFFFFFFFFu;
+    int quota = 0;
+    bool rank_ties = false;
+    if (k_cand > 0) {
+        uint32_t prefix = 0u;
+        int remaining = k_cand;
+#pragma unroll 1
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass_shift(pass);
+            const uint32_t digit_mask = pass_digit_mask(pass), hi_mask = pass_high_mask(pass);
+            clear_hist(sh);
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < B; ++u)
+                if (((cand >> u) & 1u) && (key[u] & hi_mask) == prefix)
+                    hist_add(sh, (key[u] >> shift) & digit_mask);
+            __syncthreads();
+            select_bin(sh, shift, prefix, remaining);
+        }
+        T = prefix;
+        quota = remaining;               // >= 1: ties (key == T) still to be kept
+        rank_ties = sh.ties > remaining; // more rows tie with the K-th key than may be kept
+    }
+    if (rank_ties) {
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const unsigned long long m = __ballot(((cand >> u) & 1u) && key[u] == T);
+            if (lane == 0) tie_base[u * kWaves + wave] = __popcll(m);
+        }
+        __syncthreads();
+        if (wave == 0) {  // exclusive prefix over the chunks in row order: B/4 consecutive chunks per lane
+            constexpr int kPer = kChunks / kWave;
+            int v[kPer], tot = 0;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                v[j] = tie_base[lane * kPer + j];
+                tot += v[j];
+            }
+            int incl = tot;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const int t = __shfl_up(incl, o);
+                if (lane >= o) incl += t;
+            }
+            int run = incl - tot;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) {
+                tie_base[lane * kPer + j] = run;
+                run += v[j];
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+        const int r = u * kSelectThreads + tid;
+        const int chunk = u * kWaves + wave;
+        const bool is_cand = (cand >> u) & 1u;
+        const bool tie = is_cand && key[u] == T;
+        bool keep = r < n && (!is_cand || key[u] > T);
+        const unsigned long long tie_mask = __ballot(tie);
+        // unranked: every tie is kept when any is (quota 0 only with the all-halt state, where no key is kept)
+        if (tie)
+            keep = rank_ties ? tie_base[chunk] + __popcll(tie_mask & ((1ull << lane) - 1ull)) < quota : quota > 0;
+        if (r < n) halt[r] = keep ? 0 : 1;
+        const unsigned long long m = __ballot(keep);
+        if (lane == 0 && chunk * kChunkRows < n) chunk_counts[chunk] = __popcll(m);
+    }
+}
+
 // Standalone score of Eq. 2 from a stored fp32 delta and x: one wave per row, 16-byte loads.
 template <typename T>
 __global__ __launch_bounds__(256) void score_rows_kernel(const float* __restrict__ delta, const T* __restrict__ x,
@@ -304,6 +428,29 @@ dash_status topk_static_scratch_ptr(void** out) {
     return DASH_OK;
 }
 
+// The TopK decision on n > 0 scores: up to 16384 rows in one launch that keeps the keys in registers (when the
+// caller allows it: 9 us at 8192 rows, 12.6 at 16384, where the two launches take 14; at 32768 rows it would take 23
+// against their 20, the flags of the longer input being spread over many workgroups), longer inputs by the selection
+// kernel, which leaves its state and tie counts in ws, and the flag kernel.
+static void launch_topk(const float* scores, int n, int n_first, int n_last, int k_keep, int keep_low, uint8_t* halt,
+                        int32_t* chunk_counts, void* ws, bool one_launch_allowed, hipStream_t s) {
+    if (one_launch_allowed && n <= 8 * kSelectThreads) {
+        hipLaunchKernelGGL(topk_decide_small_kernel<8>, dim3(1), dim3(kSelectThreads), 0, s, scores, n, n_first,
+                           n_last, k_keep, keep_low, halt, chunk_counts);
+    } else if (one_launch_allowed && n <= 16 * kSelectThreads) {
+        hipLaunchKernelGGL(topk_decide_small_kernel<16>, dim3(1), dim3(kSelectThreads), 0, s, scores, n, n_first,
+                           n_last, k_keep, keep_low, halt, chunk_counts);
+    } else {
+        TopkState* st = reinterpret_cast<TopkState*>(ws);
+        int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
+        const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
+        hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, n_first, n_last,
+                           k_keep, keep_low, st, tie_counts);
+        hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, n_first, n_last, keep_low,
+                           st, tie_counts, halt, chunk_counts);
+    }
+}
+
 dash_status launch_score_decide(const dash_layer_params& p, const float* partials, int n_partials, int n,
                                 float* scores, uint8_t* halt, int32_t* chunk_counts, void* ws,
                                 hipStream_t s) {
@@ -318,33 +465,22 @@ dash_status launch_score_decide(const dash_layer_params& p, const float* partial
     int64_t k_keep = p.k_keep;
     if (k_keep < 0) k_keep = dash_keep_count(n, p.rho, 0, 0, 0);
     if (k_keep > n) k_keep = n;
-    TopkState* st = reinterpret_cast<TopkState*>(ws);
-    int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
-    const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
     hipLaunchKernelGGL(score_only_kernel, dim3(blocks), dim3(256), 0, s, partials, n_partials, n,
                        p.score_kind, scores);
-    hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, (int)k_keep, 0, st, tie_counts);
-    hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, 0, st, tie_counts, halt, chunk_counts);
+    launch_topk(scores, n, p.keep_first_n, p.keep_last_n, (int)k_keep, 0, halt, chunk_counts, ws, true, s);
     return launch_status();
 }
 
 // TopK decision on scores the caller provides (any signal: the block-level one, random numbers for the random
 // control); keep_low selects the direction control.
 dash_status launch_decide_topk(const dash_layer_params& p, const float* scores, int n, int keep_low, uint8_t* halt,
-                               int32_t* chunk_counts, void* ws, hipStream_t s) {
+                               int32_t* chunk_counts, void* ws, bool one_launch_allowed, hipStream_t s) {
     if (n == 0) return DASH_OK;
     int64_t k_keep = p.k_keep;
     if (k_keep < 0) k_keep = dash_keep_count(n, p.rho, 0, 0, 0);
     if (k_keep > n) k_keep = n;
-    TopkState* st = reinterpret_cast<TopkState*>(ws);
-    int32_t* tie_counts = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(ws) + 256);
-    const int n_chunks = (n + kChunkRows - 1) / kChunkRows;
-    hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, (int)k_keep, keep_low ? 1 : 0, st, tie_counts);
-    hipLaunchKernelGGL(topk_flag_kernel, dim3(n_chunks), dim3(256), 0, s, scores, n, p.keep_first_n,
-                       p.keep_last_n, keep_low ? 1 : 0, st, tie_counts, halt, chunk_counts);
+    launch_topk(scores, n, p.keep_first_n, p.keep_last_n, (int)k_keep, keep_low ? 1 : 0, halt, chunk_counts, ws,
+                one_launch_allowed, s);
     return launch_status();
 }
 
