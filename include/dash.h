@@ -121,6 +121,14 @@ int32_t dash_norm_partials_per_row(const dash_layer_params *params);
  *                 delta_dbg: NULL, or fp32 [n,d] that receives delta
  * workspace     : device, >= dash_workspace_bytes(params, n_active), 256-byte aligned
  * profile       : NULL or a dash_profile
+ *
+ * active_idx is trusted, not checked: a check would put a pass over n values and a read-back on the path of
+ * every layer. Its values are only compared with each other (the causal mask of tiles on the diagonal), turned
+ * into rotation angles (dash_rope_qk) and copied to new_active_idx, never used as addresses, so a list that is
+ * not strictly increasing gives a mask that means nothing but no access out of bounds.
+ * dash_validate_active_idx is the check, for callers that build the list themselves.
+ * The call records kernels only (no memset, no copy, no allocation), so it can be captured in a HIP graph once
+ * dash_init() has run on the device.
  */
 dash_status dash_attn_layer(const dash_layer_params *params, const void *x, const void *q, const void *k,
                             const void *v, const void *w_o, const int32_t *active_idx, int32_t n_active,

@@ -10,6 +10,7 @@
 //   flash_fwd_mfma<DH>  bf16, MFMA 32x32x16, fp32 softmax and accumulation (the hot kernel)
 //   flash_fwd_simple<T> one wave per (row, head), plain FMA; the fp32 path
 #include "common.h"
+#include "lds_ops.h"
 #include "staging_addr.h"
 
 namespace dash {
@@ -107,15 +108,6 @@ constexpr int kFaThreads = 512;
 constexpr float kMaskedScore = -1.0e30f;
 constexpr float kRowSumLimit = 1048576.0f;  // a lane's 32-key partial row sum above this moves the softmax reference
 
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-
-// LDS transpose read: within each group of 16 lanes, lane t supplies the address of 4 consecutive
-// 16-bit elements of row t/4 (columns 4*(t%4)..+3) of a 4x16 block and receives column t of the block.
-__device__ __forceinline__ s16x4 lds_read_tr16(const __bf16* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-}
-
 // Work-item -> (query tile, head) map. Workgroups are handed to the 8 XCDs round-robin
 // (workgroup b runs on XCD b % 8) and each XCD has its own L2, so all workgroups of one XCD are given
 // the same KV head (or as few as possible): its K/V tiles are then fetched into that L2 once and shared
@@ -165,24 +157,6 @@ struct FaSmem {
     __device__ static constexpr int v_swz(int row) { return fa_v_swz(row, DH); }
 };
 
-// One direct global->LDS load: lane l's 16 bytes at `base + voff` (uniform base, per-lane 32-bit offset) land at
-// LDS address lds_base + 16*l. Issued as inline asm so that the compiler's wait-count bookkeeping does not tie
-// every later LDS read to it; the kernel waits for these loads explicitly (dma_wait) before the barrier that
-// publishes a stage. (M0 holds the LDS base; naming it as a clobber is what keeps the compiler from caching a
-// value in it.)
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma_load16(const void* base, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(base) : "memory", "m0");
-}
-#pragma clang diagnostic pop
-__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
-// waits until at most KEEP of this wave's loads (the most recently issued ones) are still in flight
-template <int KEEP>
-__device__ __forceinline__ void dma_wait_keep() { asm volatile("s_waitcnt vmcnt(%0)" : : "i"(KEEP) : "memory"); }
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
-}
 
 template <int DH>
 __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __restrict__ q,

@@ -10,6 +10,7 @@
 //
 // norm_partials layout: [P][n][2] fp32, P = column tiles of the kernel in use (256 columns; 64 in the fp32 kernel).
 #include "common.h"
+#include "lds_ops.h"
 #include "staging_addr.h"
 
 namespace dash {
@@ -117,24 +118,6 @@ constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row (conflict
 static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float) + 4 * kGM * 2 * sizeof(float),
               "epilogue staging and the row-sum exchange must fit");
 
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-
-__device__ __forceinline__ s16x4 lds_read_tr16_b(const __bf16* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p));
-}
-
-// One direct global->LDS load: lane l's 16 bytes at `base + voff` (uniform base, per-lane 32-bit offset) land at
-// LDS address lds_base + 16*l. Inline asm, so the compiler's wait-count bookkeeping does not tie every later LDS
-// read to it; the kernel waits for these loads explicitly before the barrier that publishes a stage. (M0 holds
-// the LDS base; naming it as a clobber is what keeps the compiler from caching a value in it.)
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void gemm_dma_load16(const void* base, uint32_t voff, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_base), "v"(voff), "s"(base) : "memory", "m0");
-}
-#pragma clang diagnostic pop
-__device__ __forceinline__ void gemm_dma_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 // EPI_SWIGLU: B holds gate and up columns interleaved in blocks of 32 (columns 64c..64c+31 = gate features
 // 32c..32c+31, columns 64c+32..64c+63 = the up columns of the same features), so a wave's two 32-column
@@ -240,13 +223,13 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     auto dma_next_a = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
-        for (int i = 0; i < ADMA; ++i) gemm_dma_load16(a_base, a_off[i], lds_a + so + i * 1024);
+        for (int i = 0; i < ADMA; ++i) dma_load16(a_base, a_off[i], lds_a + so + i * 1024);
         a_base += gemm_a_step_bytes();
     };
     auto dma_next_b = [&](int stage) {
         const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
 #pragma unroll
-        for (int i = 0; i < BDMA; ++i) gemm_dma_load16(b_base, b_off[i], lds_b + so + i * 1024);
+        for (int i = 0; i < BDMA; ++i) dma_load16(b_base, b_off[i], lds_b + so + i * 1024);
         b_base += b_step;
     };
 
@@ -270,8 +253,8 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
             const int krow = 32 * ks + 8 * fg + fi / 4;  // and krow + 4: the same swizzle
             const int col = wn * 64 + 16 * b + 4 * (fi % 4);
             const int scol = ((col / 8) ^ gemm_b_swz(krow)) * 8 + col % 8;
-            const s16x4 lo = lds_read_tr16_b(&sb[krow * kGN + scol]);
-            const s16x4 hi = lds_read_tr16_b(&sb[(krow + 4) * kGN + scol]);
+            const s16x4 lo = lds_read_tr16(&sb[krow * kGN + scol]);
+            const s16x4 hi = lds_read_tr16(&sb[(krow + 4) * kGN + scol]);
             bfr[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
         }
 #pragma unroll
@@ -309,7 +292,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         dma_next_b(1);
         asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepLoads) : "memory");  // step 0 has landed, step 1 may be in flight
     } else {
-        gemm_dma_wait();
+        dma_wait();
     }
     __syncthreads();
     read_frags(0, 0, Af[0], Bf[0]);
@@ -323,7 +306,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         read_frags(st, 1, Af[1], Bf[1]);
         mfma_slice(Af[0], Bf[0]);
         pin_slice();
-        gemm_dma_wait();
+        dma_wait();
         asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the second slice's fragments are in registers
         lds_barrier();
         if (kt + 2 < n_ksteps) {

@@ -339,3 +339,53 @@ def test_layer_call_in_one_launch_equals_the_staged_calls(n, d, prot):
             assert k == n
         if tau_ == float("inf"):
             assert k == min(n, prot[0] + prot[1])
+
+
+@pytest.mark.parametrize("rule", ["threshold", "topk", "none"])
+def test_layer_call_in_a_hip_graph_replays_like_eager_calls(rule):
+    """The layer call records only kernels (the words its one-launch score/decision/compaction hands chunks over
+    with are cleared by the attention kernel of the same call, not by a memset), so it can be captured in a HIP
+    graph. Every replay, with eager calls of the same library on other buffers and synchronisations in between and
+    with the inputs changed in place, must equal the eager call on the same contents bit for bit."""
+    cfg = I.LayerConfig("graph_layer", "bf16", 4000, 1500, 256, 4, 2, 64, 0.45, seed=81)
+    n = cfg.n
+    L1 = I.make_layer_inputs(cfg)
+    L2 = I.make_layer_inputs(I.scaled(cfg, n, N=cfg.N, seed=82))
+    D1, D2 = P.device_inputs(cfg, L1), P.device_inputs(cfg, L2)
+    g0 = P.run_gpu_layer(cfg, P.params_for(cfg, rule=B.RULE_NONE), D1)
+    tau, h = I.percentile_tau(g0.scores, cfg.halt_frac)
+    p = {"threshold": P.params_for(cfg, rule=B.RULE_THRESHOLD, tau=tau, keep_first_n=8, keep_last_n=4),
+         "topk": P.params_for(cfg, rule=B.RULE_TOPK, k_keep=n - h, keep_first_n=8, keep_last_n=4),
+         "none": P.params_for(cfg, rule=B.RULE_NONE)}[rule]
+    outs = ("x_next", "scores", "halt_mask", "x_compact", "new_active_idx", "n_active_out")
+
+    def eager(D):
+        buf = B.alloc_layer_buffers(p, n)
+        buf.x_compact.zero_()                      # rows past n_active_out are not written: compare like with like
+        buf.new_active_idx.zero_()
+        B.dash_attn_layer(p, D["x"], D["q"], D["k"], D["v"], D["w_o"], D["active_idx"], n, buf)
+        torch.cuda.synchronize()
+        return {k: getattr(buf, k).clone() for k in outs}
+
+    want1, want2 = eager(D1), eager(D2)
+    assert not torch.equal(want1["scores"], want2["scores"])
+    assert 0 < int(want1["n_active_out"].item()) <= n
+    G = {k: v.clone() for k, v in D1.items()}      # the graph's own input buffers
+    gbuf = B.alloc_layer_buffers(p, n)
+    B.init()
+    B.dash_attn_layer(p, G["x"], G["q"], G["k"], G["v"], G["w_o"], G["active_idx"], n, gbuf)   # eager once
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        B.dash_attn_layer(p, G["x"], G["q"], G["k"], G["v"], G["w_o"], G["active_idx"], n, gbuf)
+    for D, want in ((D1, want1), (D2, want2), (D2, want2), (D1, want1)):
+        for k in G:
+            G[k].copy_(D[k])
+        gbuf.x_compact.zero_()
+        gbuf.new_active_idx.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in outs:
+            assert torch.equal(getattr(gbuf, k), want[k]), k
+        other = eager(D2 if D is D1 else D1)        # eager work between the replays
+        assert torch.equal(other["scores"], (want2 if D is D1 else want1)["scores"])
