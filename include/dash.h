@@ -22,6 +22,12 @@
  *     dense (no padding between rows).
  *   - Errors are reported as a dash_status; argument errors are found on the host
  *     before anything is launched, HIP launch errors map to DASH_ERR_HIP.
+ *   - Largest sizes. Row counts are int32 and addresses are formed in 64 bits; two kernels
+ *     add 32-bit byte offsets to a 64-bit base, which bounds what they accept (larger
+ *     arguments return DASH_ERR_UNSUPPORTED, nothing is launched): attention with bf16
+ *     storage needs n * Hkv * dh * 2 < 2^31 bytes of K (2 097 151 rows at Hkv * dh = 512,
+ *     1 048 575 at 1024); the bf16 products need 256 * K * 2 < 2^32 and 64 * N * 2 + 512 <
+ *     2^32 for a [M,K] x [K,N] product (any M). dash_decide_topk_static has its own row limit.
  *   - dtype selects the storage type of x, q, k, v, w_o, O, x_next, x_compact:
  *     DASH_BF16 (MFMA kernels, fp32 accumulation and fp32 softmax) or DASH_F32
  *     (plain fp32 kernels). Scores and norm partials are always fp32.

@@ -653,9 +653,9 @@ template <int EPI>
 static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, int N, const __bf16* x,
                                __bf16* out, float* partials, float* delta_dbg, void* split_ws, size_t split_bytes,
                                hipStream_t s, QkvOut qkv = QkvOut{nullptr, nullptr, 0, 0}) {
-    if (init_gemm_kernels() != DASH_OK) return DASH_ERR_HIP;
     // the staging loads address a tile with 32-bit lane offsets: 256 rows of A, 64 rows of B
     if ((size_t)kGM * K * 2 >= ((size_t)1 << 32) || (size_t)kGK * N * 2 + 2 * kGN >= ((size_t)1 << 32)) return DASH_ERR_UNSUPPORTED;
+    if (init_gemm_kernels() != DASH_OK) return DASH_ERR_HIP;
     const GemmPlan g = gemm_plan(M, K, N, compute_units(), split_ws != nullptr && !delta_dbg, split_bytes);
     GemmLaunch L{};
     L.mt = g.mt;

@@ -217,3 +217,21 @@ def test_schedule_helpers_validate_arguments():
     assert B.block_cost(10, 4, 8) == 4 * 10 * 16 + 2 * 100 * 4 + 2 * 10 * 4 * 8                # App. A, Eq. 4 by hand
     assert B.schedule_cost([10, 10, 5], 4, 8) == 2 * B.block_cost(10, 4, 8) + B.block_cost(5, 4, 8)
     assert B.block_cost(-1, 4, 8) == -1.0
+
+
+def test_sizes_beyond_the_32_bit_offsets_are_reported_as_unsupported():
+    """The attention kernel adds 32-bit byte offsets to a 64-bit tile base, so K may hold at most 2^31 bytes; the
+    products bound their K and N the same way. One row more than fits must return "unsupported" from the host-side
+    checks; the largest accepted size gets past them (and fails at the launch here, where there is no GPU)."""
+    L = B.lib()
+    UNSUPPORTED, HIP = -2, -4
+    p = B.make_params(3584, 28, 4, 128, rule=B.RULE_THRESHOLD, tau=0.1)
+    limit = 2 ** 31 // (4 * 128 * 2)                       # rows whose K bytes reach 2^31
+    for n, want in ((limit - 1, HIP), (limit, UNSUPPORTED), (3 * limit, UNSUPPORTED)):
+        ws = B.workspace_bytes(p, n)
+        assert L.dash_attn_layer(ctypes.byref(p), *_layer_args(p, n, ws)) == want, n
+        assert L.dash_flash_fwd(ctypes.byref(p), FAKE, FAKE, FAKE, FAKE, n, FAKE, None) == want, n
+    # a contraction too long for the 32-bit offsets inside a 256-row operand tile: Hq * dh = 2^23
+    wide = B.make_params(3584, 65536, 65536, 128)
+    assert L.dash_wo_residual_rownorm(ctypes.byref(wide), FAKE, FAKE, FAKE, 1000, FAKE, FAKE, None, None, 0,
+                                      None) == UNSUPPORTED
