@@ -111,11 +111,17 @@ __global__ __launch_bounds__(256) void wo_simple_kernel(const T* __restrict__ A,
 // below them, 32 bytes of each) by 4 * (row % 4) + 2 * ((row / 8) % 2).
 // ------------------------------------------------------------------------------------------------
 constexpr int kGThreads = kGWaves * kWave;  // tile constants kGM, kGN, kGK: staging_addr.h
-constexpr int kGAElems = kGM * kGK, kGBElems = kGK * kGN;
-constexpr int kGStageElems = kGAElems + kGBElems;
-constexpr size_t kGemmSmemBytes = 2 * kGStageElems * sizeof(__bf16);  // two operand stages (131072 B)
+constexpr int kGBElems = kGK * kGN;
+// Operand stages in LDS: a stage holds the A tile (64 MB rows) and the B tile of one K step. The 256-row tile has
+// two stages (128 KB): the tiles of step k + 2 are requested once every wave is done with step k. The 128-row half
+// tile has three (144 KB) and requests three steps ahead: its steps are half as long, and with only one step of
+// lead it waited for memory latency at every step.
+constexpr int gemm_stages(int MB) { return MB == 2 ? 3 : 2; }
+constexpr int gemm_stage_elems(int MB) { return 64 * MB * kGK + kGBElems; }
+constexpr size_t gemm_smem_bytes(int MB) { return (size_t)gemm_stages(MB) * gemm_stage_elems(MB) * sizeof(__bf16); }
 constexpr int kEpiStr = 64 + 4;  // fp32 words per staged epilogue row (conflict-free 16-byte reads of two rows by 16 lanes)
-static_assert(kGemmSmemBytes >= 8 * 32 * kEpiStr * sizeof(float) + 4 * kGM * 2 * sizeof(float),
+static_assert(gemm_smem_bytes(4) >= 8 * 32 * kEpiStr * sizeof(float) + 4 * kGM * 2 * sizeof(float) &&
+                  gemm_smem_bytes(2) >= 8 * 32 * kEpiStr * sizeof(float) + 4 * kGM * 2 * sizeof(float),
               "epilogue staging and the row-sum exchange must fit");
 
 
@@ -165,6 +171,7 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
                                                                  GemmLaunch L, QkvOut qkv) {
     constexpr int BM = 64 * MB;   // rows of this workgroup's tile
     constexpr int WM = 32 * MB;   // rows of a wave's tile
+    constexpr int NS = gemm_stages(MB), kAElems = BM * kGK, kStageElems = gemm_stage_elems(MB);
     extern __shared__ __attribute__((aligned(16))) unsigned char gemm_smem_raw[];
     __bf16* smem = reinterpret_cast<__bf16*>(gemm_smem_raw);
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -218,16 +225,16 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     const size_t b_step = gemm_b_step_bytes(N);
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)gemm_smem_raw;
     const uint32_t lds_a = lds0 + (uint32_t)(wave * ADMA * 1024);
-    const uint32_t lds_b = lds0 + (uint32_t)(kGAElems * 2 + wave * BDMA * 1024);
+    const uint32_t lds_b = lds0 + (uint32_t)(kAElems * 2 + wave * BDMA * 1024);
     // K steps are fetched strictly in order; the A and the B tile of a step are requested separately
     auto dma_next_a = [&](int stage) {
-        const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
+        const uint32_t so = (uint32_t)(stage * kStageElems * 2);
 #pragma unroll
         for (int i = 0; i < ADMA; ++i) dma_load16(a_base, a_off[i], lds_a + so + i * 1024);
         a_base += gemm_a_step_bytes();
     };
     auto dma_next_b = [&](int stage) {
-        const uint32_t so = (uint32_t)(stage * kGStageElems * 2);
+        const uint32_t so = (uint32_t)(stage * kStageElems * 2);
 #pragma unroll
         for (int i = 0; i < BDMA; ++i) dma_load16(b_base, b_off[i], lds_b + so + i * 1024);
         b_base += b_step;
@@ -245,8 +252,8 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     const int fi = lane % 16, fg = lane / 16;
     bf16x8 Af[2][RB], Bf[2][4];
     auto read_frags = [&](int st, int ks, bf16x8* af, bf16x8* bfr) {
-        const __bf16* sa = smem + st * kGStageElems;
-        const __bf16* sb = sa + kGAElems;
+        const __bf16* sa = smem + st * kStageElems;
+        const __bf16* sb = sa + kAElems;
         // B first: the MFMAs of a slice go through the row blocks in order and need every B fragment at once
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
@@ -285,12 +292,13 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
         }
     };
     constexpr int kStepLoads = ADMA + BDMA;
-    dma_next_a(0);
-    dma_next_b(0);
-    if (n_ksteps > 1) {
-        dma_next_a(1);
-        dma_next_b(1);
-        asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kStepLoads) : "memory");  // step 0 has landed, step 1 may be in flight
+    const int n_pre = min(NS, n_ksteps);
+    for (int j = 0; j < n_pre; ++j) {
+        dma_next_a(j);
+        dma_next_b(j);
+    }
+    if (n_pre == NS) {
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 1) * kStepLoads) : "memory");  // step 0 has landed
     } else {
         dma_wait();
     }
@@ -299,23 +307,79 @@ __global__ __launch_bounds__(kGThreads, 1) void gemm_mfma_kernel(const __bf16* _
     // One round per K step of two 32-wide slices. The fragments of a slice are read while the MFMAs of the slice
     // before it run, across the step boundary too: the wait for the next step's tiles and the barrier that
     // publishes them sit before the second slice's MFMAs, whose fragments are in registers by then, and the
-    // first slice of the next step is read from the other stage while those MFMAs run. After that barrier every
-    // wave is done reading this step's stage, so the tiles of step kt + 2 are requested into it.
-    for (int kt = 0; kt < n_ksteps; ++kt) {
-        const int st = kt & 1;
+    // first slice of the next step is read from the next stage while those MFMAs run. After that barrier every
+    // wave is done reading this step's stage, so the tiles of step kt + NS are requested into it.
+    //
+    // Second half of a step. The tile requests are dealt out between its MFMAs, one every three: the compute
+    // unit's one address unit takes 16 cycles per request and holds few of them, so after a burst of requests every
+    // wave queues behind it and issues no MFMA meanwhile (a burst after the barrier: 5 % slower; one request per
+    // MFMA, per 2, per 4: 3, 1.5 and 0.5 % slower than per 3). The requests are opaque to the compiler's scheduler
+    // and fence its LDS reads, so this half is placed by hand: requests, the fragment reads of the next slice (B
+    // first) at even distances, MFMAs, pinned in eight groups.
+    auto read_b_frag = [&](int st, int ks, int b, bf16x8* bfr) {
+        const __bf16* sb = smem + st * kStageElems + kAElems;
+        const int krow = 32 * ks + 8 * fg + fi / 4;
+        const int col = wn * 64 + 16 * b + 4 * (fi % 4);
+        const int scol = ((col / 8) ^ gemm_b_swz(krow)) * 8 + col % 8;
+        const s16x4 lo = lds_read_tr16(&sb[krow * kGN + scol]);
+        const s16x4 hi = lds_read_tr16(&sb[(krow + 4) * kGN + scol]);
+        bfr[b] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    };
+    auto read_a_frag = [&](int st, int ks, int a, bf16x8* af) {
+        const __bf16* sa = smem + st * kStageElems;
+        const int row = wm * WM + 16 * a + fi;
+        af[a] = *reinterpret_cast<const bf16x8*>(&sa[row * kGK + ((4 * ks + fg) ^ ((row / 2) % 8)) * 8]);
+    };
+    constexpr int kRequestEvery = 3;  // MFMAs from one tile request to the next
+    static_assert((kStepLoads - 1) * kRequestEvery < MF, "the requests of a step fit into its second half");
+    auto second_half = [&](int st_next, bool request, int st_free) {
+        constexpr int UNITS = 4 + RB;  // fragments of the next slice: 4 B, RB A
+        const uint32_t so = (uint32_t)(st_free * kStageElems * 2);
+#pragma unroll
+        for (int m = 0; m < MF; ++m) {
+#pragma unroll
+            for (int l = 0; l < kStepLoads; ++l)
+                if (m == l * kRequestEvery && request) {
+                    if (l < ADMA) dma_load16(a_base, a_off[l], lds_a + so + l * 1024);
+                    else dma_load16(b_base, b_off[l - ADMA], lds_b + so + (l - ADMA) * 1024);
+                }
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u)  // fragment u before the first MFMA m with u * MF <= m * UNITS
+                if (u * MF <= m * UNITS && (m == 0 || u * MF > (m - 1) * UNITS)) {
+                    if (u < 4) read_b_frag(st_next, 0, u, Bf[0]);
+                    else read_a_frag(st_next, 0, u - 4, Af[0]);
+                }
+            acc[m / 4][m % 4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Af[1][m / 4], Bf[1][m % 4], acc[m / 4][m % 4], 0, 0, 0);
+            if (m % (MF / 8) == MF / 8 - 1) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (request) {
+            a_base += gemm_a_step_bytes();
+            b_base += b_step;
+        }
+    };
+    int kt = 0, st = 0;  // st = kt % NS
+    for (; kt + NS < n_ksteps; ++kt) {
+        const int st_next = st + 1 == NS ? 0 : st + 1;
+        read_frags(st, 1, Af[1], Bf[1]);
+        mfma_slice(Af[0], Bf[0]);
+        pin_slice();
+        // the tiles of step kt + 1 have landed; those of the steps after it may still be in flight
+        asm volatile("s_waitcnt vmcnt(%0)" : : "n"((NS - 2) * kStepLoads) : "memory");
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the second slice's fragments are in registers
+        lds_barrier();
+        second_half(st_next, true, st);
+        st = st_next;
+    }
+    for (; kt < n_ksteps; ++kt) {  // the last NS steps request nothing
+        const int st_next = st + 1 == NS ? 0 : st + 1;
         read_frags(st, 1, Af[1], Bf[1]);
         mfma_slice(Af[0], Bf[0]);
         pin_slice();
         dma_wait();
-        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");  // the second slice's fragments are in registers
+        asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");
         lds_barrier();
-        if (kt + 2 < n_ksteps) {
-            dma_next_a(st);
-            dma_next_b(st);
-        }
-        read_frags(st ^ 1, 0, Af[0], Bf[0]);  // after the last step: stale data, never used
-        mfma_slice(Af[1], Bf[1]);
-        pin_slice();
+        second_half(st_next, false, st);  // after the last step the fragments read are stale data, never used
+        st = st_next;
     }
     __syncthreads();  // the stale fragment reads of slower waves are harmless, but keep the epilogue's reuse simple
     // all waves are past the last barrier: the operand stages are free and are reused by the epilogue
@@ -606,14 +670,14 @@ static int compute_units() {
     return n;
 }
 
-// One-time launch attribute of every instantiation of the MFMA kernel: its 128 KB of dynamic LDS.
+// One-time launch attribute of every instantiation of the MFMA kernel: its dynamic LDS (128 KB, half tiles 144 KB).
 template <int EPI>
 static hipError_t set_gemm_lds_size() {
     hipError_t e = hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 4>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kGemmSmemBytes);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_smem_bytes(4));
     if (e != hipSuccess) return e;
     return hipFuncSetAttribute((const void*)gemm_mfma_kernel<EPI, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                               (int)kGemmSmemBytes);
+                               (int)gemm_smem_bytes(2));
 }
 
 dash_status init_gemm_kernels() {
@@ -665,7 +729,7 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
     if (g.parts >= 2) {
         float* sums = reinterpret_cast<float*>(split_ws);
         L.ksteps_per_split = g.ksteps_per_part;
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(g.tiles, g.parts), dim3(kGThreads), kGemmSmemBytes, s,
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI_SPLITK, 4>), dim3(g.tiles, g.parts), dim3(kGThreads), gemm_smem_bytes(4), s,
                            A, B, M, K, N, nullptr, nullptr, nullptr, sums, L, qkv);
         const int cols_per_wave = EPI == EPI_SWIGLU ? 1024 : 512;
         const size_t waves = (size_t)M * ((N + cols_per_wave - 1) / cols_per_wave);
@@ -676,11 +740,11 @@ static dash_status launch_gemm(const __bf16* A, const __bf16* B, int M, int K, i
     L.full = g.full;
     L.seg = g.seg;
     if (g.full > 0)
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(g.grid), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N, x,
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 4>), dim3(g.grid), dim3(kGThreads), gemm_smem_bytes(4), s, A, B, M, K, N, x,
                            out, partials, delta_dbg, L, qkv);
     if (g.rest > 0) {
         L.first_tile = g.full;
-        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * g.rest), dim3(kGThreads), kGemmSmemBytes, s, A, B, M, K, N,
+        hipLaunchKernelGGL((gemm_mfma_kernel<EPI, 2>), dim3(2 * g.rest), dim3(kGThreads), gemm_smem_bytes(2), s, A, B, M, K, N,
                            x, out, partials, delta_dbg, L, qkv);
     }
     return launch_status();
