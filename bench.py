@@ -367,7 +367,7 @@ def run_aux_kernels_bench(args, cfg):
                      "frac_of_hbm_peak": nbytes / us / 1e3 / HBM_PEAK_GBS})
     B.dash_score_rows(deltas[0], xs[0], n, d, B.DASH_BF16, B.SCORE_REL, scores)
     us_topk = timed(lambda i: B.dash_decide_topk(p, scores, n, False, halt, counts, ws))
-    rows.append({"kernel": "topk_select_kernel + topk_flag_kernel (decision on given scores, 2 launches)",
+    rows.append({"kernel": "topk_decide_small_kernel (TopK decision on 16384 given scores, one launch)",
                  "bytes": 4 * n * 2 + n, "us": us_topk, "GB/s": None, "frac_of_hbm_peak": None})
     mean_frac = sum(r["frac_of_hbm_peak"] for r in rows[:4]) / 4
     print(json.dumps({
