@@ -321,16 +321,19 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     for (int kc = 0; kc < KC; ++kc) k_elem[kc] = j * DH + ((2 * kc + h) ^ SM::k_swz(j)) * 8;
     auto qk_mfma = [&](int t) {
         const __bf16* Ks = Kst + (t & 1) * SM::STAGE_ELEMS;
+        // the two key blocks take turns, so that no MFMA accumulates into the result of the one issued just before it
+        // (eight in a row on one block measured 0.6 % slower)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) S[kb][r] = Cneg[r];
 #pragma unroll
-            for (int kc = 0; kc < KC; ++kc) {
+        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
                 const bf16x8 Kf = *reinterpret_cast<const bf16x8*>(&Ks[k_elem[kc] + 32 * kb * DH]);
                 S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Kf, Qf[kc], S[kb], 0, 0, 0);
             }
-        }
         constexpr int NM = 2 * KC;
         __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
 #pragma unroll
