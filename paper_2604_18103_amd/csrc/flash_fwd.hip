@@ -451,18 +451,8 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     for (int kc = 0; kc < KC; ++kc) asm volatile("" : "+v"(Qf[kc]));
     __syncthreads();
 
-    // Both groups run the same loop (matrix-core phase, barrier, VALU phase, barrier); group 1 is skewed
-    // by one barrier interval, so in every interval one group is in its MFMA phase and the other in its
-    // softmax phase. Number the barriers 0, 1, 2, ...: group 0 passes barrier 2t between its MFMA and
-    // softmax phases of tile t and barrier 2t+1 after the softmax phase; group 1 passes barrier 0 before
-    // its loop, then 2t+1 and 2t+2.
-    //   K(t+1), two stages: fetched by group 0 after barrier 2t-1 (K(t-1) was last read before it),
-    //     complete before barrier 2t+1, first read after it.
-    //   V(t+2), three stages: fetched by group 1 after barrier 2t+1 (V(t-1) was last read before it),
-    //     complete before barrier 2t+4; group 0 reads its first fragments in the softmax phase of tile
-    //     t+2, right after that barrier. The wave that waits always leaves the newest fetch in flight.
-    // Every wave passes the same number of barriers: waves whose rows cannot see a tile skip its work,
-    // not its barriers. The extra round t = n_tiles only drains P V of the final tile.
+    // Every wave passes the same number of barriers: waves whose rows cannot see a tile skip its work, not its
+    // barriers. The extra round t = n_tiles only drains P V of the final tile.
     // barrier that orders LDS traffic only: the staging loads in flight must not be waited for here
     auto lds_barrier = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -475,19 +465,24 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     //     group 1: softmax of tile r-1, then the MFMA stretch of tile r
     // so a SIMD sees the two roles in opposite order, and where one stretch outlasts the other the two MFMA
     // stretches may overlap instead of waiting for each other.
-    //   K(r+1) is requested by group 0 at the start of round r, V(r+1) by group 1 (so V(1) already before
-    //   the loop); both are complete before barrier r. K(r) is read in round r only: two stages. V(r) is read
-    //   in round r (first fragments, group 0's softmax) and in round r+1 (P V of tile r, group 1's first
-    //   fragments): three stages.
+    //   K(r+1) is requested by group 0 at the start of round r and complete before barrier r; K(r) is read in round
+    //   r only: two stages. V(r+1) is requested by group 1 in the middle of round r (between its softmax and its
+    //   matrix-core phase; V(0) and V(1) before the loop) and complete before barrier r; V(r) is read in round r
+    //   (first fragments, group 0's softmax) and in round r+1 (P V of tile r, group 1's first fragments): three
+    //   stages, and V(r-2)'s was last read before barrier r-1.
     for (int t = 0; t <= n_tiles; ++t) {
         if (grp == 0 && t + 1 < n_tiles) dma_next_tile((t + 1) & 1);  // K(t+1)
         mfma_phase(t);
         if (grp == 1) {
             dma_wait();  // V(t+1)
             lds_barrier();
-            if (t + 2 < n_tiles) dma_next_tile((t + 2) % 3);  // V(t+2)
         }
         valu_phase(t);
+        // V(t+2) is requested here, before group 1's matrix-core phase, not right after the barrier: there its four
+        // requests per wave met group 0's K requests in the compute unit's one address unit, and group 0's matrix-core
+        // phase started that much later (2 % of the kernel). K requests moved behind group 0's matrix-core phase
+        // as well gained nothing more.
+        if (grp == 1 && t + 2 < n_tiles) dma_next_tile((t + 2) % 3);  // V(t+2)
         if (grp == 0) {
             dma_wait();  // K(t+1)
             lds_barrier();
