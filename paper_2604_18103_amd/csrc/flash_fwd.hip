@@ -465,24 +465,24 @@ __global__ __launch_bounds__(kFaThreads, 1) void flash_fwd_mfma(const __bf16* __
     //     group 1: softmax of tile r-1, then the MFMA stretch of tile r
     // so a SIMD sees the two roles in opposite order, and where one stretch outlasts the other the two MFMA
     // stretches may overlap instead of waiting for each other.
-    //   K(r+1) is requested by group 0 at the start of round r and complete before barrier r; K(r) is read in round
-    //   r only: two stages. V(r+1) is requested by group 1 in the middle of round r (between its softmax and its
-    //   matrix-core phase; V(0) and V(1) before the loop) and complete before barrier r; V(r) is read in round r
-    //   (first fragments, group 0's softmax) and in round r+1 (P V of tile r, group 1's first fragments): three
-    //   stages, and V(r-2)'s was last read before barrier r-1.
+    //   K(r+1) is requested by group 0 in the middle of round r (after its matrix-core phase) and complete before
+    //   barrier r; K(r) is read in round r only, K(r-1) was last read before barrier r-1: two stages. V(r+1) is
+    //   requested by group 1 at the start of round r (V(0) and V(1) before the loop) and complete before barrier r;
+    //   V(r) is read in round r (first fragments, group 0's softmax) and in round r+1 (P V of tile r, group 1's first
+    //   fragments): three stages, and V(r-2) was last read before barrier r-1.
     for (int t = 0; t <= n_tiles; ++t) {
-        if (grp == 0 && t + 1 < n_tiles) dma_next_tile((t + 1) & 1);  // K(t+1)
         mfma_phase(t);
         if (grp == 1) {
             dma_wait();  // V(t+1)
             lds_barrier();
+            if (t + 2 < n_tiles) dma_next_tile((t + 2) % 3);  // V(t+2)
         }
+        // Both groups request their tile at the START OF THEIR SOFTMAX PHASE, while the other group runs MFMAs: the
+        // compute unit's one address unit takes 16 cycles per request and holds few, so a wave queues behind its
+        // group's 16 requests, and ahead of a matrix-core phase that wait leaves the matrix pipe idle (K requested
+        // before group 0's matrix-core phase, where it also met group 1's V requests: 3 % slower).
+        if (grp == 0 && t + 1 < n_tiles) dma_next_tile((t + 1) & 1);  // K(t+1)
         valu_phase(t);
-        // V(t+2) is requested here, before group 1's matrix-core phase, not right after the barrier: there its four
-        // requests per wave met group 0's K requests in the compute unit's one address unit, and group 0's matrix-core
-        // phase started that much later (2 % of the kernel). K requests moved behind group 0's matrix-core phase
-        // as well gained nothing more.
-        if (grp == 1 && t + 2 < n_tiles) dma_next_tile((t + 2) % 3);  // V(t+2)
         if (grp == 0) {
             dma_wait();  // K(t+1)
             lds_barrier();
