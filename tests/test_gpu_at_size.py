@@ -146,6 +146,34 @@ def test_residual_norm_epilogue_of_whole_tiles_every_row():
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
+@pytest.mark.parametrize("k_steps", [1, 2, 3, 4, 5, 7])
+def test_products_with_few_k_steps_through_whole_and_half_tiles(k_steps):
+    """The operand pipeline of the product kernel: the 256-row tiles keep two stages of operand tiles and request two
+    K steps ahead, the 128-row half tiles three stages and three steps ahead; prologue, steady state and the last
+    steps without requests all change with the number of K steps. A contraction of 1 ... 7 steps of 64, 512 output
+    columns and 33280 + 100 rows (260 whole tiles: 256 run as 256-row tiles, the rest and the ragged last row tile as
+    half tiles): delta on every row against the oracle's product, element by element."""
+    hq, dh, d = k_steps, 64, 512
+    n = 256 * 130 + 100
+    rng = np.random.default_rng(810 + k_steps)
+    o = I.round_to_bf16(rng.standard_normal((n, hq * dh)))
+    w = I.round_to_bf16(rng.standard_normal((hq * dh, d)) / np.sqrt(hq * dh))
+    x = I.round_to_bf16(rng.standard_normal((n, d)))
+    p = B.make_params(d, hq, hq, dh)
+    P_ = B.norm_partials_per_row(p)
+    delta = ref.project(o, w)
+    xn = torch.empty((n, d), dtype=torch.bfloat16, device="cuda")
+    parts = torch.full((P_, n, 2), float("nan"), dtype=torch.float32, device="cuda")
+    dd = torch.full((n, d), float("nan"), dtype=torch.float32, device="cuda")
+    B.dash_wo_residual_rownorm(p, _dev(o), _dev(w), _dev(x), n, xn, parts, dd, None)
+    torch.cuda.synchronize()
+    got = dd.cpu().numpy()
+    assert np.abs(got - delta).max() <= 1e-5 * np.abs(delta).max()      # fp32 sums of exact bf16 products
+    assert P.row_rel_err(_f(xn), ref.residual(x, delta)).max() <= P.X_TOL["bf16"]
+    sums = parts.double().sum(dim=0).cpu().numpy()
+    np.testing.assert_allclose(sums[:, 0], (delta ** 2).sum(axis=1), rtol=1e-4)
+
+
 def test_gated_epilogue_of_whole_tiles_every_row():
     """Feed-forward with hidden 256 and width 1792: the gate/up product has 3584 columns (266 tiles, gating in the
     epilogue of 256-row tiles); every row against the oracle."""
